@@ -1,0 +1,133 @@
+/* liboptireduce_hip -- the per-node compute path of OptiReduce (arXiv 2310.06993) on one MI355X.
+ *
+ * The path: a gradient bucket is encoded with a randomized Hadamard transform before it is cut into
+ * N shards and sent (Sec. 3.3; Sec. 3 overview); the node that owns shard r averages the r-th shards
+ * of all workers over the entries that the bounded transport delivered (Sec. 3.1.1); the aggregated
+ * bucket is decoded (Sec. 3.3; Sec. 4: encode before, decode after the reduction).
+ *
+ * Conventions common to every call
+ *   - Every pointer is a DEVICE pointer owned by the caller.  The library allocates nothing, keeps no
+ *     state between calls and may be called from several host threads.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call validates its
+ *     arguments on the host, enqueues its kernels on that stream and returns; it never synchronises.
+ *     On any error nothing is enqueued and no output is touched.
+ *   - Vectors are contiguous.  fp32 data is `float`; bf16 data is passed as uint16_t bit patterns.
+ *     Data pointers must be 16-byte aligned, mask pointers 4-byte aligned.
+ *   - block_log2 = k selects the transform block B = 2^k, OR_MIN_LOG2 <= k <= OR_MAX_LOG2.
+ *   - The random diagonal: entry i of the padded vector (i counted from `base_index` for the first
+ *     entry passed) is multiplied by -1 iff bit (i mod 128) of Philox4x32-10(counter = (i div 128,
+ *     0, 0) as (lo32, hi32, 0, 0), key = (seed lo32, seed hi32)) is set, bits counted from the least
+ *     significant bit of output word 0.  Every worker must use the same seed for a bucket.
+ *     `base_index` must be a multiple of max(B, 128).
+ *   - The Hadamard matrix is in natural (Sylvester) order, H[u][v] = (-1)^popcount(u & v), scaled by
+ *     B^(-1/2) on encode and on decode.
+ *   - Masks: one row of shard_len/32 uint32 words per worker; bit j of word w is entry 32w + j;
+ *     1 = the entry arrived.  The data slot of an entry that did not arrive is never used in
+ *     arithmetic and may hold anything (NaN included).
+ *   - A length of 0 is valid and does nothing.
+ */
+#ifndef OPTIREDUCE_H_
+#define OPTIREDUCE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int or_status;
+enum {
+  OR_OK = 0,
+  OR_ERR_NULL = 1,      /* a required pointer is NULL                                          */
+  OR_ERR_BLOCK = 2,     /* block_log2 outside [OR_MIN_LOG2, OR_MAX_LOG2]                       */
+  OR_ERR_WORKERS = 3,   /* N < 1 or N > OR_MAX_WORKERS                                         */
+  OR_ERR_SHAPE = 4,     /* length not a multiple of what the call needs, bad base_index,
+                           forbidden overlap, length too large                                */
+  OR_ERR_ALIGN = 5,     /* a pointer is not aligned as required                                */
+  OR_ERR_WORKSPACE = 6, /* workspace missing or smaller than or_workspace_bytes() says         */
+  OR_ERR_HIP = 7        /* a launch failed; or_last_hip_error() gives the hipError_t           */
+};
+
+#define OR_MIN_LOG2 5
+#define OR_MAX_LOG2 16
+#define OR_MAX_WORKERS 255
+
+/* ---- helpers (host only, no GPU work) ------------------------------------------------------- */
+
+/* n rounded up to a whole number of blocks of 2^block_log2 entries (0 if block_log2 is invalid). */
+uint64_t or_padded_len(uint64_t n, int block_log2);
+/* Bytes of device workspace that or_reduce_decode* / or_fused_path* need for this shard length and
+ * block size: 0 for block_log2 <= 14, else room for the fp32 sums/means and the counts. */
+size_t or_workspace_bytes(uint64_t shard_len, int block_log2);
+const char* or_status_string(or_status s);
+int or_version(void);
+/* hipError_t (as int) of the last failed launch on the calling thread, 0 if none. */
+int or_last_hip_error(void);
+
+/* ---- Sec. 3.3 encode: out = B^(-1/2) H D grad, blockwise ------------------------------------
+ * grad: n entries.  out: or_padded_len(n) entries; the pad of the last block is treated as zeros
+ * before the transform.  out == grad is allowed iff n is already a multiple of B; any other overlap
+ * is an error.  or_rht_encode is or_rht_encode_at with base_index 0. */
+or_status or_rht_encode(const float* grad, uint64_t n, int block_log2, uint64_t seed, float* out, void* stream);
+or_status or_rht_encode_at(const float* grad, uint64_t n, int block_log2, uint64_t seed, uint64_t base_index,
+                           float* out, void* stream);
+/* bf16 gradient in, bf16 encoded out (fp32 arithmetic, one rounding to nearest even at the store). */
+or_status or_rht_encode_bf16(const uint16_t* grad, uint64_t n, int block_log2, uint64_t seed, uint64_t base_index,
+                             uint16_t* out, void* stream);
+
+/* ---- Sec. 3.1.1 aggregation at the owner of a shard ------------------------------------------
+ * shards: [N][shard_len] row-major, row i = worker i's copy of the shard.  masks: [N][shard_len/32].
+ * sum_out[e] = sum over workers whose bit e is set (fp32 accumulation, increasing worker index);
+ * count_out[e] = how many were set.  shard_len must be a multiple of 32.  Outputs must not overlap
+ * the inputs. */
+or_status or_masked_reduce(const float* shards, const uint32_t* masks, int N, uint64_t shard_len, float* sum_out,
+                           uint8_t* count_out, void* stream);
+or_status or_masked_reduce_bf16(const uint16_t* shards, const uint32_t* masks, int N, uint64_t shard_len,
+                                float* sum_out, uint8_t* count_out, void* stream);
+
+/* ---- Sec. 3.3 / Sec. 4 decode: out = D B^(-1/2) H agg, first n entries kept -------------------
+ * agg: or_padded_len(n) fp32 entries, already the mean.  out: n entries.  In place allowed iff n is
+ * a multiple of B. */
+or_status or_rht_decode(const float* agg, uint64_t n, int block_log2, uint64_t seed, float* out, void* stream);
+or_status or_rht_decode_at(const float* agg, uint64_t n, int block_log2, uint64_t seed, uint64_t base_index,
+                           float* out, void* stream);
+or_status or_rht_decode_bf16(const float* agg, uint64_t n, int block_log2, uint64_t seed, uint64_t base_index,
+                             uint16_t* out, void* stream);
+
+/* ---- fused forms (same results as the calls above chained, fewer trips through memory) --------
+ * "Averages" (Sec. 3.1.1) is read as sum / number received, 0 where nothing was received.
+ *
+ * or_finalize_decode: mean = sum / count, then decode.  sum, count: or_padded_len(n) entries. */
+or_status or_finalize_decode(const float* sum, const uint8_t* count, uint64_t n, int block_log2, uint64_t seed,
+                             uint64_t base_index, float* out, void* stream);
+or_status or_finalize_decode_bf16(const float* sum, const uint8_t* count, uint64_t n, int block_log2,
+                                  uint64_t seed, uint64_t base_index, uint16_t* out, void* stream);
+
+/* or_reduce_decode: masked aggregation of N encoded shards, mean, decode of that shard.
+ * shard_len must be a multiple of B.  out: shard_len entries of the shards' type.  count_out may be
+ * NULL.  workspace: device memory of or_workspace_bytes(shard_len, block_log2) bytes, 256-byte
+ * aligned, or NULL when that is 0; its contents afterwards are unspecified. */
+or_status or_reduce_decode(const float* shards, const uint32_t* masks, int N, uint64_t shard_len, int block_log2,
+                           uint64_t seed, uint64_t base_index, float* out, uint8_t* count_out, void* workspace,
+                           size_t workspace_bytes, void* stream);
+or_status or_reduce_decode_bf16(const uint16_t* shards, const uint32_t* masks, int N, uint64_t shard_len,
+                                int block_log2, uint64_t seed, uint64_t base_index, uint16_t* out,
+                                uint8_t* count_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/* or_fused_path: the whole path for the shard one node owns, with all N workers' RAW (not yet
+ * encoded) slices of that shard resident: encode each slice, keep what arrived, sum and count,
+ * mean, decode.  grads: [N][shard_len] raw gradient slices; the encoded value is rounded to the
+ * wire type (fp32: no-op; bf16: nearest even) before it is summed, as if it had been stored by
+ * or_rht_encode*.  Other arguments as for or_reduce_decode. */
+or_status or_fused_path(const float* grads, const uint32_t* masks, int N, uint64_t shard_len, int block_log2,
+                        uint64_t seed, uint64_t base_index, float* out, uint8_t* count_out, void* workspace,
+                        size_t workspace_bytes, void* stream);
+or_status or_fused_path_bf16(const uint16_t* grads, const uint32_t* masks, int N, uint64_t shard_len,
+                             int block_log2, uint64_t seed, uint64_t base_index, uint16_t* out, uint8_t* count_out,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OPTIREDUCE_H_ */

@@ -1,0 +1,170 @@
+"""Thin ctypes binding of liboptireduce_hip.so: argument marshalling only.
+
+Every function has the name and argument order of its C entry point in include/optireduce.h and
+takes torch tensors that already live on the GPU (torch is used for device memory and streams,
+nothing else).  A non-zero status raises OptiReduceError.  There is no CPU fallback: if the
+library is not built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liboptireduce_hip.so")
+if not os.path.exists(_LIB_PATH):
+    raise ImportError(
+        "liboptireduce_hip.so is not built (%s); run `python -m paper_2310_06993_amd.build`" % _LIB_PATH)
+lib = C.CDLL(_LIB_PATH)
+
+_u64, _int, _p, _sz = C.c_uint64, C.c_int, C.c_void_p, C.c_size_t
+
+OR_OK = 0
+OR_MIN_LOG2, OR_MAX_LOG2, OR_MAX_WORKERS = 5, 16, 255
+
+_SIGS = {
+    "or_padded_len": (_u64, [_u64, _int]),
+    "or_workspace_bytes": (_sz, [_u64, _int]),
+    "or_status_string": (C.c_char_p, [_int]),
+    "or_version": (_int, []),
+    "or_last_hip_error": (_int, []),
+    "or_rht_encode": (_int, [_p, _u64, _int, _u64, _p, _p]),
+    "or_rht_encode_at": (_int, [_p, _u64, _int, _u64, _u64, _p, _p]),
+    "or_rht_encode_bf16": (_int, [_p, _u64, _int, _u64, _u64, _p, _p]),
+    "or_masked_reduce": (_int, [_p, _p, _int, _u64, _p, _p, _p]),
+    "or_masked_reduce_bf16": (_int, [_p, _p, _int, _u64, _p, _p, _p]),
+    "or_rht_decode": (_int, [_p, _u64, _int, _u64, _p, _p]),
+    "or_rht_decode_at": (_int, [_p, _u64, _int, _u64, _u64, _p, _p]),
+    "or_rht_decode_bf16": (_int, [_p, _u64, _int, _u64, _u64, _p, _p]),
+    "or_finalize_decode": (_int, [_p, _p, _u64, _int, _u64, _u64, _p, _p]),
+    "or_finalize_decode_bf16": (_int, [_p, _p, _u64, _int, _u64, _u64, _p, _p]),
+    "or_reduce_decode": (_int, [_p, _p, _int, _u64, _int, _u64, _u64, _p, _p, _p, _sz, _p]),
+    "or_reduce_decode_bf16": (_int, [_p, _p, _int, _u64, _int, _u64, _u64, _p, _p, _p, _sz, _p]),
+    "or_fused_path": (_int, [_p, _p, _int, _u64, _int, _u64, _u64, _p, _p, _p, _sz, _p]),
+    "or_fused_path_bf16": (_int, [_p, _p, _int, _u64, _int, _u64, _u64, _p, _p, _p, _sz, _p]),
+}
+for _name, (_res, _args) in _SIGS.items():
+    _f = getattr(lib, _name)
+    _f.restype, _f.argtypes = _res, _args
+
+
+class OptiReduceError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: status %d (%s)" % (where, status, lib.or_status_string(status).decode()))
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("liboptireduce_hip takes device tensors")
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _check(status, where):
+    if status != OR_OK:
+        raise OptiReduceError(status, where)
+
+
+def or_padded_len(n: int, block_log2: int) -> int:
+    return int(lib.or_padded_len(n, block_log2))
+
+
+def or_workspace_bytes(shard_len: int, block_log2: int) -> int:
+    return int(lib.or_workspace_bytes(shard_len, block_log2))
+
+
+def or_version() -> int:
+    return int(lib.or_version())
+
+
+def or_rht_encode(grad, n, block_log2, seed, out, stream=None):
+    _check(lib.or_rht_encode(_ptr(grad), n, block_log2, seed, _ptr(out), _stream(stream)), "or_rht_encode")
+
+
+def or_rht_encode_at(grad, n, block_log2, seed, base_index, out, stream=None):
+    _check(lib.or_rht_encode_at(_ptr(grad), n, block_log2, seed, base_index, _ptr(out), _stream(stream)),
+           "or_rht_encode_at")
+
+
+def or_rht_encode_bf16(grad, n, block_log2, seed, base_index, out, stream=None):
+    _check(lib.or_rht_encode_bf16(_ptr(grad), n, block_log2, seed, base_index, _ptr(out), _stream(stream)),
+           "or_rht_encode_bf16")
+
+
+def or_masked_reduce(shards, masks, N, shard_len, sum_out, count_out, stream=None):
+    _check(lib.or_masked_reduce(_ptr(shards), _ptr(masks), N, shard_len, _ptr(sum_out), _ptr(count_out),
+                                _stream(stream)), "or_masked_reduce")
+
+
+def or_masked_reduce_bf16(shards, masks, N, shard_len, sum_out, count_out, stream=None):
+    _check(lib.or_masked_reduce_bf16(_ptr(shards), _ptr(masks), N, shard_len, _ptr(sum_out), _ptr(count_out),
+                                     _stream(stream)), "or_masked_reduce_bf16")
+
+
+def or_rht_decode(agg, n, block_log2, seed, out, stream=None):
+    _check(lib.or_rht_decode(_ptr(agg), n, block_log2, seed, _ptr(out), _stream(stream)), "or_rht_decode")
+
+
+def or_rht_decode_at(agg, n, block_log2, seed, base_index, out, stream=None):
+    _check(lib.or_rht_decode_at(_ptr(agg), n, block_log2, seed, base_index, _ptr(out), _stream(stream)),
+           "or_rht_decode_at")
+
+
+def or_rht_decode_bf16(agg, n, block_log2, seed, base_index, out, stream=None):
+    _check(lib.or_rht_decode_bf16(_ptr(agg), n, block_log2, seed, base_index, _ptr(out), _stream(stream)),
+           "or_rht_decode_bf16")
+
+
+def or_finalize_decode(total, count, n, block_log2, seed, base_index, out, stream=None):
+    _check(lib.or_finalize_decode(_ptr(total), _ptr(count), n, block_log2, seed, base_index, _ptr(out),
+                                  _stream(stream)), "or_finalize_decode")
+
+
+def or_finalize_decode_bf16(total, count, n, block_log2, seed, base_index, out, stream=None):
+    _check(lib.or_finalize_decode_bf16(_ptr(total), _ptr(count), n, block_log2, seed, base_index, _ptr(out),
+                                       _stream(stream)), "or_finalize_decode_bf16")
+
+
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    return _ptr(workspace), workspace.numel() * workspace.element_size()
+
+
+def or_reduce_decode(shards, masks, N, shard_len, block_log2, seed, base_index, out, count_out=None,
+                     workspace=None, stream=None):
+    w, wb = _ws(workspace)
+    _check(lib.or_reduce_decode(_ptr(shards), _ptr(masks), N, shard_len, block_log2, seed, base_index, _ptr(out),
+                                _ptr(count_out), w, wb, _stream(stream)), "or_reduce_decode")
+
+
+def or_reduce_decode_bf16(shards, masks, N, shard_len, block_log2, seed, base_index, out, count_out=None,
+                          workspace=None, stream=None):
+    w, wb = _ws(workspace)
+    _check(lib.or_reduce_decode_bf16(_ptr(shards), _ptr(masks), N, shard_len, block_log2, seed, base_index,
+                                     _ptr(out), _ptr(count_out), w, wb, _stream(stream)), "or_reduce_decode_bf16")
+
+
+def or_fused_path(grads, masks, N, shard_len, block_log2, seed, base_index, out, count_out=None, workspace=None,
+                  stream=None):
+    w, wb = _ws(workspace)
+    _check(lib.or_fused_path(_ptr(grads), _ptr(masks), N, shard_len, block_log2, seed, base_index, _ptr(out),
+                             _ptr(count_out), w, wb, _stream(stream)), "or_fused_path")
+
+
+def or_fused_path_bf16(grads, masks, N, shard_len, block_log2, seed, base_index, out, count_out=None,
+                       workspace=None, stream=None):
+    w, wb = _ws(workspace)
+    _check(lib.or_fused_path_bf16(_ptr(grads), _ptr(masks), N, shard_len, block_log2, seed, base_index, _ptr(out),
+                                  _ptr(count_out), w, wb, _stream(stream)), "or_fused_path_bf16")

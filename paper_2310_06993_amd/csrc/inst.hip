@@ -1,0 +1,53 @@
+// One block-size class of kernels (compile with -DOR_K=0, 11, 12, ... 16).
+#include "launch_table.hpp"
+
+#ifndef OR_K
+#error "compile with -DOR_K=<class>"
+#endif
+
+namespace orhost {
+using namespace ordev;
+
+namespace {
+constexpr int K = OR_K;
+typedef Geo<K> G;
+
+#define OR_LAUNCHER(name, kernel)                                                            \
+  hipError_t name(const PathArgs& a, unsigned long long units, hipStream_t s) {             \
+    if (units == 0) return hipSuccess;                                                       \
+    if (units > 0x7FFFFFFFull) return hipErrorInvalidValue;                                  \
+    hipLaunchKernelGGL(kernel, dim3((unsigned)units), dim3(G::THREADS), 0, s, a);            \
+    return hipGetLastError();                                                                \
+  }
+
+OR_LAUNCHER(enc_f32, (k_encode<K, float, float>))
+OR_LAUNCHER(enc_bf16, (k_encode<K, bf16_t, bf16_t>))
+OR_LAUNCHER(dec_f32, (k_decode<K, float, false>))
+OR_LAUNCHER(dec_bf16, (k_decode<K, bf16_t, false>))
+OR_LAUNCHER(fdec_f32, (k_decode<K, float, true>))
+OR_LAUNCHER(fdec_bf16, (k_decode<K, bf16_t, true>))
+#if OR_K <= 14
+OR_LAUNCHER(rdec_f32, (k_reduce_decode<K, float, float>))
+OR_LAUNCHER(rdec_bf16, (k_reduce_decode<K, bf16_t, bf16_t>))
+OR_LAUNCHER(fus_f32, (k_fused<K, float, true>))
+OR_LAUNCHER(fus_bf16, (k_fused<K, bf16_t, true>))
+#else
+OR_LAUNCHER(fus_f32, (k_fused<K, float, false>))
+OR_LAUNCHER(fus_bf16, (k_fused<K, bf16_t, false>))
+#endif
+}  // namespace
+
+#if !defined(__HIP_DEVICE_COMPILE__)
+#define OR_CAT2(a, b) a##b
+#define OR_CAT(a, b) OR_CAT2(a, b)
+extern const KernelTable OR_CAT(or_kernel_table_, OR_K) = {
+    G::TL, enc_f32, enc_bf16, dec_f32, dec_bf16, fdec_f32, fdec_bf16,
+#if OR_K <= 14
+    rdec_f32, rdec_bf16,
+#else
+    nullptr, nullptr,
+#endif
+    fus_f32, fus_bf16};
+#endif
+
+}  // namespace orhost

@@ -1,0 +1,356 @@
+// C ABI of liboptireduce_hip: argument checks and kernel dispatch.  Semantics are stated in
+// include/optireduce.h; nothing here allocates or synchronises.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <math.h>
+
+#include "../../include/optireduce.h"
+#include "launch_table.hpp"
+
+namespace orhost {
+extern const KernelTable or_kernel_table_0, or_kernel_table_11, or_kernel_table_12, or_kernel_table_13,
+    or_kernel_table_14, or_kernel_table_15, or_kernel_table_16;
+
+const KernelTable* table_for_class(int cls) {
+  switch (cls) {
+    case 0: return &or_kernel_table_0;
+    case 11: return &or_kernel_table_11;
+    case 12: return &or_kernel_table_12;
+    case 13: return &or_kernel_table_13;
+    case 14: return &or_kernel_table_14;
+    case 15: return &or_kernel_table_15;
+    case 16: return &or_kernel_table_16;
+    default: return nullptr;
+  }
+}
+}  // namespace orhost
+
+namespace {
+using ordev::PathArgs;
+using ordev::u64;
+
+thread_local int g_last_hip_error = 0;
+
+// ------------------------------------------------------------------ streaming masked sum + count
+// Sec. 3.1.1 aggregation with no transform around it: each lane owns VEC consecutive entries (16
+// bytes of one worker's shard), reads the VEC mask bits of every worker and adds under select.
+template <class Wire, int VEC>
+__global__ __launch_bounds__(256) void k_masked_reduce(const Wire* __restrict__ shards,
+                                                       const uint32_t* __restrict__ masks, int N, u64 L,
+                                                       float* __restrict__ sum_out, uint8_t* __restrict__ count_out) {
+  const u64 e = ((u64)blockIdx.x * 256 + threadIdx.x) * VEC;
+  if (e >= L) return;
+  typedef Wire vec_t __attribute__((ext_vector_type(VEC)));
+  const u64 words = L >> 5;
+  float acc[VEC];
+  uint32_t cnt[VEC];
+#pragma unroll
+  for (int j = 0; j < VEC; ++j) { acc[j] = 0.0f; cnt[j] = 0; }
+  const int sh = (int)(e & 31);
+  int i = 0;
+  for (; i + 4 <= N; i += 4) {
+    vec_t x[4];
+    uint32_t m[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      x[u] = *(const vec_t*)(shards + (u64)(i + u) * L + e);
+      m[u] = masks[(u64)(i + u) * words + (e >> 5)] >> sh;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) {
+        const bool got = (m[u] >> j) & 1u;
+        float f;
+        if constexpr (sizeof(Wire) == 4) f = x[u][j]; else f = __builtin_bit_cast(float, (uint32_t)x[u][j] << 16);
+        acc[j] += got ? f : 0.0f;
+        cnt[j] += got ? 1u : 0u;
+      }
+  }
+  for (; i < N; ++i) {
+    vec_t x = *(const vec_t*)(shards + (u64)i * L + e);
+    uint32_t m = masks[(u64)i * words + (e >> 5)] >> sh;
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+      const bool got = (m >> j) & 1u;
+      float f;
+      if constexpr (sizeof(Wire) == 4) f = x[j]; else f = __builtin_bit_cast(float, (uint32_t)x[j] << 16);
+      acc[j] += got ? f : 0.0f;
+      cnt[j] += got ? 1u : 0u;
+    }
+  }
+  typedef float f4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+  for (int j = 0; j < VEC; j += 4) *(f4*)(sum_out + e + j) = f4{acc[j], acc[j + 1], acc[j + 2], acc[j + 3]};
+#pragma unroll
+  for (int j = 0; j < VEC; j += 4)
+    *(uint32_t*)(count_out + e + j) = cnt[j] | (cnt[j + 1] << 8) | (cnt[j + 2] << 16) | (cnt[j + 3] << 24);
+}
+
+template <class Wire, int VEC>
+hipError_t launch_masked_reduce(const void* shards, const uint32_t* masks, int N, u64 L, float* sum_out,
+                                uint8_t* count_out, hipStream_t s) {
+  if (L == 0) return hipSuccess;
+  const u64 threads = (L + VEC - 1) / VEC;
+  const u64 blocks = (threads + 255) / 256;
+  if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((k_masked_reduce<Wire, VEC>), dim3((unsigned)blocks), dim3(256), 0, s, (const Wire*)shards,
+                     masks, N, L, sum_out, count_out);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ checks
+bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+bool valid_k(int k) { return k >= OR_MIN_LOG2 && k <= OR_MAX_LOG2; }
+int class_of(int k) { return k <= 10 ? 0 : k; }
+
+bool ranges_overlap(const void* a, u64 abytes, const void* b, u64 bbytes) {
+  uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+  return a0 < b0 + bbytes && b0 < a0 + abytes;
+}
+
+or_status finish(hipError_t e) {
+  if (e == hipSuccess) return OR_OK;
+  g_last_hip_error = (int)e;
+  return OR_ERR_HIP;
+}
+
+u64 padded(u64 n, int k) {
+  const u64 B = (u64)1 << k;
+  return (n + B - 1) / B * B;
+}
+
+float scale_of(int k) { return (float)(1.0 / sqrt((double)((u64)1 << k))); }
+
+or_status check_base(int k, u64 base) {
+  const u64 B = (u64)1 << k;
+  const u64 q = B > 128 ? B : 128;
+  return (base % q) ? OR_ERR_SHAPE : OR_OK;
+}
+
+// vector transforms: `in_es`/`out_es` are element sizes; the side of length n_pad is the encoded one
+or_status check_transform(const void* in, u64 in_len, int in_es, void* out, u64 out_len, int out_es, int k, u64 base) {
+  if (!valid_k(k)) return OR_ERR_BLOCK;
+  if (check_base(k, base)) return OR_ERR_SHAPE;
+  if (in_len == 0 && out_len == 0) return OR_OK;
+  if (!in || !out) return OR_ERR_NULL;
+  if (!aligned(in, 16) || !aligned(out, 16)) return OR_ERR_ALIGN;
+  if (in_len > ((u64)1 << 46) || out_len > ((u64)1 << 46)) return OR_ERR_SHAPE;
+  if (ranges_overlap(in, in_len * in_es, out, out_len * out_es)) {
+    const bool exact_in_place = (in == out) && in_len == out_len && in_es == out_es && k <= 14;
+    if (!exact_in_place) return OR_ERR_SHAPE;
+  }
+  return OR_OK;
+}
+
+template <class T>
+or_status encode_impl(const T* grad, u64 n, int k, u64 seed, u64 base, T* out, void* stream, bool bf16) {
+  const u64 n_pad = valid_k(k) ? padded(n, k) : 0;
+  if (or_status s = check_transform(grad, n, sizeof(T), out, n_pad, sizeof(T), k, base)) return s;
+  if (n == 0) return OR_OK;
+  const orhost::KernelTable* t = orhost::table_for_class(class_of(k));
+  PathArgs a = {};
+  a.in = grad; a.out = out; a.n = n; a.n_pad = n_pad; a.seed = seed; a.base = base; a.k = k; a.scale = scale_of(k);
+  const u64 units = (n_pad + ((u64)1 << t->tile_log2) - 1) >> t->tile_log2;
+  return finish((bf16 ? t->encode_bf16 : t->encode_f32)(a, units, (hipStream_t)stream));
+}
+
+template <class T>
+or_status decode_impl(const float* agg, const uint8_t* count, bool finalize, u64 n, int k, u64 seed, u64 base, T* out,
+                      void* stream, bool bf16) {
+  const u64 n_pad = valid_k(k) ? padded(n, k) : 0;
+  if (or_status s = check_transform(agg, n_pad, 4, out, n, sizeof(T), k, base)) return s;
+  if (n == 0) return OR_OK;
+  if (finalize) {
+    if (!count) return OR_ERR_NULL;
+    if (ranges_overlap(count, n_pad, out, n * sizeof(T))) return OR_ERR_SHAPE;
+  }
+  const orhost::KernelTable* t = orhost::table_for_class(class_of(k));
+  PathArgs a = {};
+  a.in = agg; a.count_in = count; a.out = out; a.n = n; a.n_pad = n_pad; a.seed = seed; a.base = base; a.k = k;
+  a.scale = scale_of(k);
+  const u64 units = (n_pad + ((u64)1 << t->tile_log2) - 1) >> t->tile_log2;
+  orhost::launch_fn f = finalize ? (bf16 ? t->finalize_decode_bf16 : t->finalize_decode_f32)
+                                 : (bf16 ? t->decode_bf16 : t->decode_f32);
+  return finish(f(a, units, (hipStream_t)stream));
+}
+
+or_status check_reduce(const void* shards, const uint32_t* masks, int N, u64 L, int es) {
+  if (N < 1 || N > OR_MAX_WORKERS) return OR_ERR_WORKERS;
+  if (L % 32) return OR_ERR_SHAPE;
+  if (L > ((u64)1 << 40)) return OR_ERR_SHAPE;
+  if (L == 0) return OR_OK;
+  if (!shards || !masks) return OR_ERR_NULL;
+  if (!aligned(shards, 16) || !aligned(masks, 4)) return OR_ERR_ALIGN;
+  if ((L * es) % 16) return OR_ERR_SHAPE;  // every worker's row must start 16-byte aligned
+  return OR_OK;
+}
+
+template <class T>
+or_status masked_reduce_impl(const T* shards, const uint32_t* masks, int N, u64 L, float* sum_out, uint8_t* count_out,
+                             void* stream) {
+  if (or_status s = check_reduce(shards, masks, N, L, sizeof(T))) return s;
+  if (L == 0) return OR_OK;
+  if (!sum_out || !count_out) return OR_ERR_NULL;
+  if (!aligned(sum_out, 16) || !aligned(count_out, 4)) return OR_ERR_ALIGN;
+  const u64 in_bytes = (u64)N * L * sizeof(T), mask_bytes = (u64)N * (L / 8);
+  if (ranges_overlap(sum_out, L * 4, shards, in_bytes) || ranges_overlap(count_out, L, shards, in_bytes) ||
+      ranges_overlap(sum_out, L * 4, masks, mask_bytes) || ranges_overlap(count_out, L, masks, mask_bytes) ||
+      ranges_overlap(sum_out, L * 4, count_out, L))
+    return OR_ERR_SHAPE;
+  constexpr int VEC = 16 / sizeof(T);
+  return finish(launch_masked_reduce<T, VEC>(shards, masks, N, L, sum_out, count_out, (hipStream_t)stream));
+}
+
+size_t workspace_bytes(u64 L, int k) {
+  if (!valid_k(k) || k <= 14) return 0;
+  const u64 sums = (L * 4 + 255) / 256 * 256;
+  const u64 counts = (L + 255) / 256 * 256;
+  return (size_t)(sums + counts);
+}
+
+// shared front of or_reduce_decode* and or_fused_path*
+template <class T>
+or_status path_impl(bool fused, const T* in, const uint32_t* masks, int N, u64 L, int k, u64 seed, u64 base, T* out,
+                    uint8_t* count_out, void* ws, size_t ws_bytes, void* stream, bool bf16) {
+  if (!valid_k(k)) return OR_ERR_BLOCK;
+  if (or_status s = check_reduce(in, masks, N, L, sizeof(T))) return s;
+  if (L % ((u64)1 << k)) return OR_ERR_SHAPE;
+  if (check_base(k, base)) return OR_ERR_SHAPE;
+  if (L == 0) return OR_OK;
+  if (!out) return OR_ERR_NULL;
+  if (!aligned(out, 16)) return OR_ERR_ALIGN;
+  const u64 in_bytes = (u64)N * L * sizeof(T), mask_bytes = (u64)N * (L / 8);
+  if (ranges_overlap(out, L * sizeof(T), in, in_bytes) || ranges_overlap(out, L * sizeof(T), masks, mask_bytes))
+    return OR_ERR_SHAPE;
+  if (count_out && (ranges_overlap(count_out, L, in, in_bytes) || ranges_overlap(count_out, L, masks, mask_bytes) ||
+                    ranges_overlap(count_out, L, out, L * sizeof(T))))
+    return OR_ERR_SHAPE;
+  const size_t need = workspace_bytes(L, k);
+  if (need) {
+    if (!ws || ws_bytes < need) return OR_ERR_WORKSPACE;
+    if (!aligned(ws, 256)) return OR_ERR_ALIGN;
+    if (ranges_overlap(ws, need, in, in_bytes) || ranges_overlap(ws, need, masks, mask_bytes) ||
+        ranges_overlap(ws, need, out, L * sizeof(T)) || (count_out && ranges_overlap(ws, need, count_out, L)))
+      return OR_ERR_SHAPE;
+  }
+  const orhost::KernelTable* t = orhost::table_for_class(class_of(k));
+  hipStream_t s = (hipStream_t)stream;
+  const u64 units = (L + ((u64)1 << t->tile_log2) - 1) >> t->tile_log2;
+  PathArgs a = {};
+  a.in = in; a.masks = masks; a.out = out; a.count_out = count_out; a.n = L; a.n_pad = L; a.seed = seed; a.base = base;
+  a.N = N; a.k = k; a.scale = scale_of(k);
+  if (!need) {
+    orhost::launch_fn f = fused ? (bf16 ? t->fused_bf16 : t->fused_f32) : (bf16 ? t->reduce_decode_bf16 : t->reduce_decode_f32);
+    return finish(f(a, units, s));
+  }
+  // a block spans several tiles: stop at the mean (or sum and count) in the workspace, then decode it
+  float* ws_f32 = (float*)ws;
+  uint8_t* ws_cnt = (uint8_t*)ws + (L * 4 + 255) / 256 * 256;
+  PathArgs d = {};
+  d.out = out; d.n = L; d.n_pad = L; d.seed = seed; d.base = base; d.k = k; d.scale = a.scale;
+  d.in = ws_f32;
+  if (fused) {
+    a.mean_out = ws_f32;
+    a.out = nullptr;
+    if (hipError_t e = (bf16 ? t->fused_bf16 : t->fused_f32)(a, units, s)) return finish(e);
+    return finish((bf16 ? t->decode_bf16 : t->decode_f32)(d, units, s));
+  }
+  uint8_t* cnt = count_out ? count_out : ws_cnt;
+  constexpr int VEC = 16 / sizeof(T);
+  if (hipError_t e = launch_masked_reduce<T, VEC>(in, masks, N, L, ws_f32, cnt, s)) return finish(e);
+  d.count_in = cnt;
+  return finish((bf16 ? t->finalize_decode_bf16 : t->finalize_decode_f32)(d, units, s));
+}
+
+}  // namespace
+
+extern "C" {
+
+uint64_t or_padded_len(uint64_t n, int block_log2) { return valid_k(block_log2) ? padded(n, block_log2) : 0; }
+size_t or_workspace_bytes(uint64_t shard_len, int block_log2) { return workspace_bytes(shard_len, block_log2); }
+int or_version(void) { return 100; }
+int or_last_hip_error(void) { return g_last_hip_error; }
+
+const char* or_status_string(or_status s) {
+  switch (s) {
+    case OR_OK: return "ok";
+    case OR_ERR_NULL: return "a required pointer is NULL";
+    case OR_ERR_BLOCK: return "block_log2 out of range";
+    case OR_ERR_WORKERS: return "worker count out of range";
+    case OR_ERR_SHAPE: return "bad length, base_index or overlap";
+    case OR_ERR_ALIGN: return "pointer not aligned";
+    case OR_ERR_WORKSPACE: return "workspace missing or too small";
+    case OR_ERR_HIP: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+or_status or_rht_encode(const float* grad, uint64_t n, int block_log2, uint64_t seed, float* out, void* stream) {
+  return encode_impl<float>(grad, n, block_log2, seed, 0, out, stream, false);
+}
+or_status or_rht_encode_at(const float* grad, uint64_t n, int block_log2, uint64_t seed, uint64_t base_index,
+                           float* out, void* stream) {
+  return encode_impl<float>(grad, n, block_log2, seed, base_index, out, stream, false);
+}
+or_status or_rht_encode_bf16(const uint16_t* grad, uint64_t n, int block_log2, uint64_t seed, uint64_t base_index,
+                             uint16_t* out, void* stream) {
+  return encode_impl<uint16_t>(grad, n, block_log2, seed, base_index, out, stream, true);
+}
+
+or_status or_masked_reduce(const float* shards, const uint32_t* masks, int N, uint64_t shard_len, float* sum_out,
+                           uint8_t* count_out, void* stream) {
+  return masked_reduce_impl<float>(shards, masks, N, shard_len, sum_out, count_out, stream);
+}
+or_status or_masked_reduce_bf16(const uint16_t* shards, const uint32_t* masks, int N, uint64_t shard_len,
+                                float* sum_out, uint8_t* count_out, void* stream) {
+  return masked_reduce_impl<uint16_t>(shards, masks, N, shard_len, sum_out, count_out, stream);
+}
+
+or_status or_rht_decode(const float* agg, uint64_t n, int block_log2, uint64_t seed, float* out, void* stream) {
+  return decode_impl<float>(agg, nullptr, false, n, block_log2, seed, 0, out, stream, false);
+}
+or_status or_rht_decode_at(const float* agg, uint64_t n, int block_log2, uint64_t seed, uint64_t base_index,
+                           float* out, void* stream) {
+  return decode_impl<float>(agg, nullptr, false, n, block_log2, seed, base_index, out, stream, false);
+}
+or_status or_rht_decode_bf16(const float* agg, uint64_t n, int block_log2, uint64_t seed, uint64_t base_index,
+                             uint16_t* out, void* stream) {
+  return decode_impl<uint16_t>(agg, nullptr, false, n, block_log2, seed, base_index, out, stream, true);
+}
+
+or_status or_finalize_decode(const float* sum, const uint8_t* count, uint64_t n, int block_log2, uint64_t seed,
+                             uint64_t base_index, float* out, void* stream) {
+  return decode_impl<float>(sum, count, true, n, block_log2, seed, base_index, out, stream, false);
+}
+or_status or_finalize_decode_bf16(const float* sum, const uint8_t* count, uint64_t n, int block_log2,
+                                  uint64_t seed, uint64_t base_index, uint16_t* out, void* stream) {
+  return decode_impl<uint16_t>(sum, count, true, n, block_log2, seed, base_index, out, stream, true);
+}
+
+or_status or_reduce_decode(const float* shards, const uint32_t* masks, int N, uint64_t shard_len, int block_log2,
+                           uint64_t seed, uint64_t base_index, float* out, uint8_t* count_out, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+  return path_impl<float>(false, shards, masks, N, shard_len, block_log2, seed, base_index, out, count_out, workspace,
+                          workspace_bytes, stream, false);
+}
+or_status or_reduce_decode_bf16(const uint16_t* shards, const uint32_t* masks, int N, uint64_t shard_len,
+                                int block_log2, uint64_t seed, uint64_t base_index, uint16_t* out,
+                                uint8_t* count_out, void* workspace, size_t workspace_bytes, void* stream) {
+  return path_impl<uint16_t>(false, shards, masks, N, shard_len, block_log2, seed, base_index, out, count_out,
+                             workspace, workspace_bytes, stream, true);
+}
+or_status or_fused_path(const float* grads, const uint32_t* masks, int N, uint64_t shard_len, int block_log2,
+                        uint64_t seed, uint64_t base_index, float* out, uint8_t* count_out, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+  return path_impl<float>(true, grads, masks, N, shard_len, block_log2, seed, base_index, out, count_out, workspace,
+                          workspace_bytes, stream, false);
+}
+or_status or_fused_path_bf16(const uint16_t* grads, const uint32_t* masks, int N, uint64_t shard_len,
+                             int block_log2, uint64_t seed, uint64_t base_index, uint16_t* out, uint8_t* count_out,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+  return path_impl<uint16_t>(true, grads, masks, N, shard_len, block_log2, seed, base_index, out, count_out, workspace,
+                             workspace_bytes, stream, true);
+}
+
+}  // extern "C"

@@ -1,0 +1,332 @@
+"""HIP path vs CPU oracle, element by element, on seeded inputs (sizes the oracle does in seconds).
+
+fp32 results must agree to a relative L2 error of 1e-6, bf16 results to 1e-2; sign draws, masks
+and received counts must agree bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+from _util import TOL, as_f64, dev, masks_to_dev, pack_mask_np, rel_l2, to_np
+
+pytestmark = pytest.mark.gpu
+
+ALL_K = list(range(5, 17))
+
+
+@pytest.fixture(scope="module")
+def b():
+    import paper_2310_06993_amd.binding as binding
+    assert torch.cuda.is_available()
+    return binding
+
+
+def _bf16_bits(x32: np.ndarray) -> np.ndarray:
+    return to_np(torch.from_numpy(x32).to(torch.bfloat16))
+
+
+def _dev_bf16(bits: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(bits.view(np.int16).copy()).to(dev()).view(torch.bfloat16)
+
+
+def _sizes(k):
+    """Lengths that span several tiles and end in a ragged block."""
+    B = 1 << k
+    tile = max(B, 1024) if k <= 14 else 1 << 14
+    return [B * 3 - 5, max(3 * tile, 2 * B) + B + 17]
+
+
+# ------------------------------------------------------------------ encode / decode
+@pytest.mark.parametrize("k", ALL_K)
+def test_encode_decode_fp32(b, orc, k):
+    B = 1 << k
+    rng = np.random.default_rng(k)
+    for n in _sizes(k):
+        seed, base = 1000 + k, max(B, 128) * 3
+        x = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+        n_pad = b.or_padded_len(n, k)
+        assert n_pad == orc.padded_len(n, k)
+        xd = torch.from_numpy(x).to(dev())
+        enc = torch.full((n_pad,), float("nan"), device=dev())
+        b.or_rht_encode_at(xd, n, k, seed, base, enc)
+        want = orc.rht_encode(x, k, seed, base)
+        assert rel_l2(to_np(enc), want) <= TOL["f32"], (k, n)
+        y = (rng.standard_normal(n_pad) * 1e-3).astype(np.float32)
+        dec = torch.full((n,), float("nan"), device=dev())
+        b.or_rht_decode_at(torch.from_numpy(y).to(dev()), n, k, seed, base, dec)
+        assert rel_l2(to_np(dec), orc.rht_decode(y, n, k, seed, base)) <= TOL["f32"], (k, n)
+        # base_index 0 entry points
+        if n == _sizes(k)[0]:
+            b.or_rht_encode(xd, n, k, seed, enc)
+            assert rel_l2(to_np(enc), orc.rht_encode(x, k, seed, 0)) <= TOL["f32"]
+            b.or_rht_decode(enc.clone(), n, k, seed, dec)
+            assert rel_l2(to_np(dec), x) <= 2 * TOL["f32"]
+
+
+@pytest.mark.parametrize("k", [5, 8, 10, 11, 12, 13, 14, 15, 16])
+def test_encode_decode_bf16(b, orc, k):
+    B = 1 << k
+    rng = np.random.default_rng(50 + k)
+    n = _sizes(k)[1]
+    seed, base = 77, max(B, 128)
+    x = _bf16_bits((rng.standard_normal(n) * 1e-4).astype(np.float32))
+    n_pad = b.or_padded_len(n, k)
+    enc = torch.zeros(n_pad, dtype=torch.bfloat16, device=dev())
+    b.or_rht_encode_bf16(_dev_bf16(x), n, k, seed, base, enc)
+    want = orc.rht_encode(x, k, seed, base)
+    assert rel_l2(to_np(enc), want) <= TOL["bf16"]
+    # stricter: the two may differ only where fp32 vs fp64 arithmetic straddles a bf16 rounding boundary
+    assert (to_np(enc) != want).mean() < 0.02
+    y = (rng.standard_normal(n_pad) * 1e-4).astype(np.float32)
+    dec = torch.zeros(n, dtype=torch.bfloat16, device=dev())
+    b.or_rht_decode_bf16(torch.from_numpy(y).to(dev()), n, k, seed, base, dec)
+    want = orc.rht_decode(y, n, k, seed, base, out_dtype=np.uint16)
+    assert rel_l2(to_np(dec), want) <= TOL["bf16"]
+    assert (to_np(dec) != want).mean() < 0.02
+
+
+@pytest.mark.parametrize("k", [6, 10, 12, 14, 16])
+def test_sign_draws_are_bit_exact(b, orc, k):
+    # decode of sqrt(B) * e_0 in every block is exactly the sign vector (even k: all values exact)
+    B = 1 << k
+    n = 5 * B if k < 14 else 2 * B
+    seed, base = (0xABCDEF << 24) + k, 7 * max(B, 128)
+    agg = np.zeros(n, np.float32)
+    agg[::B] = np.sqrt(B)
+    out = torch.empty(n, device=dev())
+    b.or_rht_decode_at(torch.from_numpy(agg).to(dev()), n, k, seed, base, out)
+    want = 1.0 - 2.0 * orc.sign_bits(seed, base, n).astype(np.float32)
+    assert np.array_equal(to_np(out), want)
+
+
+def test_sign_stream_beyond_2_to_32(b, orc):
+    k, base, seed = 12, (1 << 33) + (1 << 12) * 5, 99
+    n = 1 << 13
+    agg = np.zeros(n, np.float32)
+    agg[:: 1 << k] = 64.0
+    out = torch.empty(n, device=dev())
+    b.or_rht_decode_at(torch.from_numpy(agg).to(dev()), n, k, seed, base, out)
+    assert np.array_equal(to_np(out), 1.0 - 2.0 * orc.sign_bits(seed, base, n).astype(np.float32))
+
+
+@pytest.mark.parametrize("k", [6, 8, 10, 12, 14, 16])
+def test_integer_round_trip_is_bit_exact(b, k):
+    # H(Hx) = Bx: with small integers and even k every intermediate is exact in fp32
+    B = 1 << k
+    n = 3 * B
+    x = torch.randint(-3, 4, (n,), device=dev(), generator=torch.Generator(device=dev()).manual_seed(k)).float()
+    enc = torch.empty(n, device=dev())
+    dec = torch.empty(n, device=dev())
+    b.or_rht_encode(x, n, k, 5, enc)
+    b.or_rht_decode(enc, n, k, 5, dec)
+    assert torch.equal(dec, x)
+    # Parseval on the GPU result
+    assert abs(float(enc.double().norm() / x.double().norm()) - 1.0) < 1e-6
+    if k <= 14:  # in place is allowed when the length is whole blocks
+        y = x.clone()
+        b.or_rht_encode(y, n, k, 5, y)
+        assert torch.equal(y, enc)
+        b.or_rht_decode(y, n, k, 5, y)
+        assert torch.equal(y, x)
+
+
+# ------------------------------------------------------------------ aggregation
+@pytest.mark.parametrize("N,L", [(1, 32), (3, 96), (4, 32 * 257), (8, 32 * 1000 + 64), (16, 4096 * 3), (255, 64)])
+@pytest.mark.parametrize("kind", ["f32", "bf16"])
+def test_masked_reduce(b, orc, N, L, kind):
+    rng = np.random.default_rng(N * 1000 + L)
+    x = rng.standard_normal((N, L)).astype(np.float32)
+    recv = rng.random((N, L)) > 0.2
+    masks = pack_mask_np(recv)
+    total = torch.empty(L, device=dev())
+    count = torch.empty(L, dtype=torch.uint8, device=dev())
+    if kind == "f32":
+        shards = x
+        poisoned = np.where(recv, x, np.nan).astype(np.float32)   # lost slots hold NaN: never read
+        b.or_masked_reduce(torch.from_numpy(poisoned).to(dev()), masks_to_dev(masks), N, L, total, count)
+    else:
+        shards = _bf16_bits(x)
+        poisoned = np.where(recv, shards, 0x7FC0).astype(np.uint16)
+        b.or_masked_reduce_bf16(_dev_bf16(poisoned), masks_to_dev(masks), N, L, total, count)
+    want_sum, want_count = orc.masked_reduce(shards, masks)
+    assert np.array_equal(to_np(count), want_count)
+    assert np.isfinite(to_np(total)).all()
+    assert rel_l2(to_np(total), want_sum) <= TOL["f32"]
+
+
+@pytest.mark.parametrize("k", [5, 9, 10, 12, 14, 16])
+def test_finalize_decode(b, orc, k):
+    B = 1 << k
+    n = _sizes(k)[0]
+    n_pad = b.or_padded_len(n, k)
+    rng = np.random.default_rng(k + 300)
+    total = rng.standard_normal(n_pad).astype(np.float32)
+    count = rng.integers(0, 9, n_pad).astype(np.uint8)
+    seed, base = 31, 2 * max(B, 128)
+    want = orc.rht_decode(orc.finalize(total, count), n, k, seed, base)
+    out = torch.empty(n, device=dev())
+    b.or_finalize_decode(torch.from_numpy(total).to(dev()), torch.from_numpy(count).to(dev()), n, k, seed, base, out)
+    assert rel_l2(to_np(out), want) <= TOL["f32"]
+    outh = torch.empty(n, dtype=torch.bfloat16, device=dev())
+    b.or_finalize_decode_bf16(torch.from_numpy(total).to(dev()), torch.from_numpy(count).to(dev()), n, k, seed, base,
+                              outh)
+    assert rel_l2(to_np(outh), orc.rht_decode(orc.finalize(total, count), n, k, seed, base, out_dtype=np.uint16)) \
+        <= TOL["bf16"]
+
+
+def _workspace(b, L, k):
+    nbytes = b.or_workspace_bytes(L, k)
+    return torch.empty(nbytes, dtype=torch.uint8, device=dev()) if nbytes else None
+
+
+@pytest.mark.parametrize("k,N,blocks", [(5, 3, 70), (7, 4, 9), (10, 4, 5), (11, 8, 3), (12, 8, 3), (13, 2, 2),
+                                        (14, 5, 2), (15, 3, 2), (16, 4, 2)])
+@pytest.mark.parametrize("kind", ["f32", "bf16"])
+def test_reduce_decode_and_fused(b, orc, k, N, blocks, kind):
+    B = 1 << k
+    L = blocks * B
+    rng = np.random.default_rng(k * 100 + N)
+    raw32 = (rng.standard_normal((N, L)) * 1e-3).astype(np.float32)
+    recv = rng.random((N, L)) > 0.03
+    recv[:, 5 * 32: 6 * 32] = False          # a word nobody delivered: count 0 -> mean 0
+    recv[1 % N, : L // 2] = rng.random(L // 2) > 0.5
+    masks = pack_mask_np(recv)
+    md = masks_to_dev(masks)
+    seed, base = 4242 + k, 3 * max(B, 128)
+    ws = _workspace(b, L, k)
+    count = torch.empty(L, dtype=torch.uint8, device=dev())
+    if kind == "f32":
+        raw = raw32
+        want, want_count = orc.fused_path(raw, masks, k, seed, base)
+        out = torch.empty(L, device=dev())
+        b.or_fused_path(torch.from_numpy(raw).to(dev()), md, N, L, k, seed, base, out, count, ws)
+        assert np.array_equal(to_np(count), want_count)
+        assert rel_l2(to_np(out), want) <= TOL["f32"]
+        # encoded shards in, decoded shard out; NaN in the slots that never arrived
+        enc = np.stack([orc.rht_encode(raw[i], k, seed, base) for i in range(N)])
+        encd = torch.from_numpy(np.where(recv, enc, np.nan).astype(np.float32)).to(dev())
+        out2 = torch.empty(L, device=dev())
+        count.zero_()
+        b.or_reduce_decode(encd, md, N, L, k, seed, base, out2, count, ws)
+        assert np.array_equal(to_np(count), want_count)
+        assert rel_l2(to_np(out2), want) <= TOL["f32"]
+        # count_out is optional
+        out3 = torch.empty(L, device=dev())
+        b.or_fused_path(torch.from_numpy(raw).to(dev()), md, N, L, k, seed, base, out3, None, ws)
+        assert torch.equal(out3, out)
+    else:
+        raw = _bf16_bits(raw32)
+        want, want_count = orc.fused_path(raw, masks, k, seed, base)
+        out = torch.empty(L, dtype=torch.bfloat16, device=dev())
+        b.or_fused_path_bf16(_dev_bf16(raw), md, N, L, k, seed, base, out, count, ws)
+        assert np.array_equal(to_np(count), want_count)
+        assert rel_l2(to_np(out), want) <= TOL["bf16"]
+        enc = np.stack([orc.rht_encode(raw[i], k, seed, base) for i in range(N)])
+        out2 = torch.empty(L, dtype=torch.bfloat16, device=dev())
+        b.or_reduce_decode_bf16(_dev_bf16(np.where(recv, enc, 0x7FC0).astype(np.uint16)), md, N, L, k, seed, base,
+                                out2, count, ws)
+        assert np.array_equal(to_np(count), want_count)
+        assert rel_l2(to_np(out2), want) <= TOL["bf16"]
+        # with the encoded shards given, only fp32-vs-fp64 summation differs: much tighter than 1e-2
+        assert (to_np(out2) != want).mean() < 0.02
+
+
+def test_three_calls_equal_fused(b, orc):
+    from paper_2310_06993_amd import workloads as wl
+    cfg = wl.CONFIGS["tiny"]
+    N, L, k = cfg.workers, cfg.shard_len(), cfg.block_log2
+    assert (N, L, k) == (4, 16384, 10)
+    g = wl.make_grads(cfg, dev(), shard=1)
+    m = wl.make_masks(cfg, dev(), shard=1)
+    seed, base = cfg.seed, 1 * L
+    enc = torch.empty((N, L), device=dev())
+    for i in range(N):
+        b.or_rht_encode_at(g[i], L, k, seed, base, enc[i])
+    total = torch.empty(L, device=dev())
+    count = torch.empty(L, dtype=torch.uint8, device=dev())
+    b.or_masked_reduce(enc, m, N, L, total, count)
+    mean = torch.where(count > 0, total / count.float().clamp(min=1), torch.zeros_like(total))
+    out3 = torch.empty(L, device=dev())
+    b.or_rht_decode_at(mean, L, k, seed, base, out3)
+    outf = torch.empty(L, device=dev())
+    countf = torch.empty(L, dtype=torch.uint8, device=dev())
+    b.or_fused_path(g, m, N, L, k, seed, base, outf, countf)
+    assert torch.equal(count, countf)
+    want, want_count = orc.fused_path(to_np(g), to_np(m), k, seed, base)
+    assert np.array_equal(to_np(count), want_count)
+    assert rel_l2(to_np(out3), want) <= TOL["f32"] and rel_l2(to_np(outf), want) <= TOL["f32"]
+    # about 1% of the entries of the other three workers are missing; the owner's are all there
+    lost = 1.0 - to_np(count).astype(np.float64).mean() / N
+    assert 0.004 < lost < 0.011 and to_np(count).min() >= 1
+
+
+def test_no_drops_gives_exact_mean_of_integers(b):
+    k, N = 12, 8
+    L = 3 << k
+    g = torch.randint(-4, 5, (N, L), device=dev(), generator=torch.Generator(device=dev()).manual_seed(3)).float()
+    m = torch.full((N, L // 32), -1, dtype=torch.int32, device=dev())
+    out = torch.empty(L, device=dev())
+    count = torch.empty(L, dtype=torch.uint8, device=dev())
+    b.or_fused_path(g, m, N, L, k, 9, 0, out, count)
+    assert torch.equal(out, g.mean(dim=0)) and bool((count == N).all())
+
+
+def test_tail_drop_is_dispersed(b, orc):
+    # the paper's motivating pattern: the tail of one worker's shard never arrives
+    from paper_2310_06993_amd import workloads as wl
+    k, N = 10, 4
+    L = 8 << k
+    rng = np.random.default_rng(21)
+    g = (rng.standard_normal((N, L)) * 1e-3).astype(np.float32)
+    m = wl.tail_drop_masks(N, L, worker=2, fraction=0.1, device=dev())
+    out = torch.empty(L, device=dev())
+    count = torch.empty(L, dtype=torch.uint8, device=dev())
+    b.or_fused_path(torch.from_numpy(g).to(dev()), m, N, L, k, 6, 0, out, count)
+    want, want_count = orc.fused_path(g, to_np(m), k, 6, 0)
+    assert np.array_equal(to_np(count), want_count) and rel_l2(to_np(out), want) <= TOL["f32"]
+    assert int((to_np(count) == N - 1).sum()) == int(L * 0.1) // 32 * 32
+
+
+# ------------------------------------------------------------------ edges
+def test_empty_inputs_and_streams(b):
+    z = torch.empty(0, device=dev())
+    b.or_rht_encode(z, 0, 10, 1, z)
+    b.or_rht_decode(z, 0, 10, 1, z)
+    b.or_masked_reduce(z, torch.empty(0, dtype=torch.int32, device=dev()), 4, 0, z,
+                       torch.empty(0, dtype=torch.uint8, device=dev()))
+    b.or_fused_path(z, torch.empty(0, dtype=torch.int32, device=dev()), 4, 0, 10, 1, 0, z, None)
+    # a caller stream other than the current one
+    s = torch.cuda.Stream()
+    n, k = 5000, 8
+    x = torch.randn(n, device=dev())
+    enc1 = torch.empty(b.or_padded_len(n, k), device=dev())
+    enc2 = torch.empty_like(enc1)
+    b.or_rht_encode(x, n, k, 3, enc1)
+    torch.cuda.synchronize()
+    b.or_rht_encode(x, n, k, 3, enc2, stream=s)
+    s.synchronize()
+    assert torch.equal(enc1, enc2)
+
+
+def test_errors_leave_outputs_untouched(b):
+    n, k = 4096, 12
+    x = torch.randn(n, device=dev())
+    out = torch.full((n,), 7.0, device=dev())
+    with pytest.raises(b.OptiReduceError) as e:
+        b.or_rht_encode(x, n, 3, 1, out)
+    assert e.value.status == 2
+    with pytest.raises(b.OptiReduceError) as e:
+        b.or_rht_encode_at(x, n, k, 1, 100, out)
+    assert e.value.status == 4
+    with pytest.raises(b.OptiReduceError) as e:
+        b.or_rht_encode(x[1:], n - 1, k, 1, out)      # misaligned input
+    assert e.value.status == 5
+    with pytest.raises(b.OptiReduceError) as e:
+        b.or_rht_encode(x, n - 100, k, 1, x)          # in place needs whole blocks
+    assert e.value.status == 4
+    with pytest.raises(b.OptiReduceError) as e:
+        b.or_fused_path(torch.zeros((2, 1 << 16), device=dev()), torch.zeros((2, 2048), dtype=torch.int32, device=dev()),
+                        2, 1 << 16, 16, 1, 0, torch.zeros(1 << 16, device=dev()), None, None)
+    assert e.value.status == 6
+    torch.cuda.synchronize()
+    assert bool((out == 7.0).all())
