@@ -1,0 +1,207 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused OptiReduce node path (RHT encode -> masked aggregate -> mean -> decode).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-extra] [--no-cpu]
+
+One step = one pass of the whole path (sign flip, blockwise Hadamard, masked sum and count, mean,
+inverse transform) over one synthetic batch: the N workers' raw slices of the shard this node owns,
+already resident in HBM.  The headline workload is the ResNet-50-sized configuration; input sets are
+rotated so that consecutive steps do not find their inputs in the 256 MB last-level cache.  Prints
+ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published
+LLC_BYTES = 256 << 20       # last-level (Infinity) cache the rotation has to defeat
+
+
+def build_sets(wl, b, cfg, device, nsets, entries=None, first=0):
+    """nsets independent input sets for one launch shape: (grads, masks, out, count, workspace)."""
+    sets = []
+    L = cfg.shard_len(entries)
+    for s in range(nsets):
+        g = wl.make_grads(cfg, device, shard=s % cfg.workers, entries=entries, first=first)
+        m = wl.make_masks(cfg, device, shard=s % cfg.workers, entries=entries, salt=s)
+        out = torch.empty(L, dtype=g.dtype, device=device)
+        cnt = torch.empty(L, dtype=torch.uint8, device=device)
+        nws = b.or_workspace_bytes(L, cfg.block_log2)
+        ws = torch.empty(nws, dtype=torch.uint8, device=device) if nws else None
+        sets.append((g, m, out, cnt, ws))
+    return sets
+
+
+def launch(b, cfg, L, st, shard):
+    g, m, out, cnt, ws = st
+    fn = b.or_fused_path if cfg.dtype == "f32" else b.or_fused_path_bf16
+    fn(g, m, cfg.workers, L, cfg.block_log2, cfg.seed, shard * L, out, cnt, ws)
+
+
+def time_fused(wl, b, cfg, device, steps, warmup, entries=None, launches_per_step=1, max_bytes=24 << 30):
+    """Times `steps` steps; a step is `launches_per_step` back-to-back launches (buckets) of one shape.
+    Returns (seconds per step by wall clock, mean seconds per launch by HIP events, bytes per launch)."""
+    L = cfg.shard_len(entries)
+    es = 4 if cfg.dtype == "f32" else 2
+    per_launch = wl.bytes_fused(cfg.workers, L, es)
+    footprint = cfg.workers * L * es + cfg.workers * L // 8 + L * (es + 1) + b.or_workspace_bytes(L, cfg.block_log2)
+    nsets = max(2, min(-(-3 * LLC_BYTES // footprint), 64))
+    nsets = max(1, min(nsets, max_bytes // footprint))
+    sets = build_sets(wl, b, cfg, device, nsets, entries)
+    torch.cuda.synchronize()
+    it = 0
+    for _ in range(warmup * launches_per_step):
+        launch(b, cfg, L, sets[it % nsets], it % nsets % cfg.workers)
+        it += 1
+    torch.cuda.synchronize()
+    total = steps * launches_per_step
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(total)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for j in range(total):
+        ev[j][0].record()
+        launch(b, cfg, L, sets[it % nsets], it % nsets % cfg.workers)
+        ev[j][1].record()
+        it += 1
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kern = float(np.mean([a.elapsed_time(z) for a, z in ev])) * 1e-3
+    return (t1 - t0) / steps, kern, per_launch, nsets, sets
+
+
+def cpu_baseline(wl, b, cfg, sets, target_seconds=12.0):
+    """The oracle, single-threaded on this host, on the first blocks of the same workload; also
+    checks the GPU result of those blocks against it."""
+    import oracle
+    g, m, out, cnt, _ = sets[0]
+    B, N, k = cfg.block, cfg.workers, cfg.block_log2
+    L = g.shape[1]
+
+    def run(nblocks):
+        n = nblocks * B
+        gh = g[:, :n].contiguous().cpu()
+        gh = gh.view(torch.int16).numpy().view(np.uint16) if gh.dtype == torch.bfloat16 else gh.numpy()
+        mh = m[:, : n // 32].contiguous().cpu().numpy().view(np.uint32)
+        t0 = time.perf_counter()
+        want, wcnt = oracle.fused_path(gh, mh, k, cfg.seed, 0)
+        return time.perf_counter() - t0, want, wcnt
+
+    probe = max(1, min(4, L // B))
+    t_probe, _, _ = run(probe)
+    nblocks = int(max(probe, min(L // B, target_seconds / max(t_probe / probe, 1e-9))))
+    secs, want, wcnt = run(nblocks)
+    n = nblocks * B
+    got = out[:n].cpu()
+    got = (got.view(torch.int16).numpy().view(np.uint16).astype(np.uint32) << 16).view(np.float32) \
+        if got.dtype == torch.bfloat16 else got.numpy()
+    wantf = (want.astype(np.uint32) << 16).view(np.float32) if want.dtype == np.uint16 else want
+    rel = float(np.linalg.norm(got.astype(np.float64) - wantf) / np.linalg.norm(wantf.astype(np.float64)))
+    counts_equal = bool(np.array_equal(cnt[:n].cpu().numpy(), wcnt))
+    es = 4 if cfg.dtype == "f32" else 2
+    return {
+        "value": wl.bytes_fused(N, n, es) / secs / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "host_cores": os.cpu_count(), "entries_per_s": N * n / secs, "seconds": secs,
+        "sample": "first %d blocks of 2^%d entries x %d workers of the %s workload (%d of %d input entries)"
+                  % (nblocks, k, N, cfg.name, N * n, N * L),
+        "gpu_vs_oracle_rel_l2_on_sample": rel, "counts_bit_exact_on_sample": counts_equal,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-extra", action="store_true", help="skip the other model-sized workloads")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--workload", default="resnet50")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the node path has no collective); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+
+    import paper_2310_06993_amd.binding as b
+    from paper_2310_06993_amd import workloads as wl
+
+    device = torch.device("cuda:0")
+    torch.cuda.set_device(device)
+    cfg = wl.CONFIGS[args.workload]
+    es = 4 if cfg.dtype == "f32" else 2
+
+    per_step, kern, nbytes, nsets, sets = time_fused(wl, b, cfg, device, args.steps, args.warmup)
+    L = cfg.shard_len()
+    # make sure the set the oracle is compared with holds this run's output
+    launch(b, cfg, L, sets[0], 0)
+    torch.cuda.synchronize()
+
+    result = {
+        "metric": "GB/s and gradient entries/s, fused RHT+masked reduce; % of HBM peak",
+        "value": nbytes / per_step / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": per_step * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if cfg.dtype == "f32" else "bf16 in/out, f32 arithmetic",
+        "data": "synthetic",
+        "entries_per_s": cfg.workers * L / per_step,
+        "pct_hbm_peak": 100.0 * nbytes / per_step / 1e9 / HBM_PEAK_GBPS,
+        "config": {"workload": "%s-sized: N=%d workers, %s, P=%d, shard_len=%d, block 2^%d, %s drops %.0f%%"
+                               % (cfg.name, cfg.workers, cfg.dtype, cfg.entries, L, cfg.block_log2, cfg.drops,
+                                  cfg.loss * 100),
+                   "entry_point": "or_fused_path" if cfg.dtype == "f32" else "or_fused_path_bf16",
+                   "input_sets_rotated": nsets, "bytes_per_step": nbytes},
+        "roofline": {"bound": "hbm", "achieved": nbytes / kern / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": nbytes / kern / 1e9 / HBM_PEAK_GBPS, "traffic": None,
+                     "kernel": "k_fused", "avg_launch_us": kern * 1e6},
+    }
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(wl, b, cfg, sets)
+    del sets
+    torch.cuda.empty_cache()
+
+    if not args.no_extra:
+        extra = []
+        for name, steps in (("bert_large", 20), ("gpt2_xl", 3), ("llama_8b", 5)):
+            if name == args.workload:
+                continue
+            c = wl.CONFIGS[name]
+            try:
+                if c.bucket_entries:
+                    nb = len(c.buckets())
+                    ps, kn, by, ns, st = time_fused(wl, b, c, device, steps, 1, entries=c.bucket_entries,
+                                                    launches_per_step=nb)
+                    by_step = by * nb   # the short last bucket is counted as a full one: a few % high on bytes AND time
+                    ent = c.workers * c.shard_len(c.bucket_entries) * nb
+                    note = "%d back-to-back launches of one 25 MiB bucket shape per step" % nb
+                else:
+                    ps, kn, by, ns, st = time_fused(wl, b, c, device, steps, 2)
+                    by_step, ent, note = by, c.workers * c.shard_len(), "one launch per step"
+                extra.append({"workload": name, "GB_per_s": by_step / ps / 1e9, "entries_per_s": ent / ps,
+                              "ms_per_step": ps * 1e3, "avg_launch_us": kn * 1e6,
+                              "launch_GB_per_s": by / kn / 1e9, "frac_hbm_peak": by / kn / 1e9 / HBM_PEAK_GBPS,
+                              "input_sets_rotated": ns, "note": note})
+                del st
+                torch.cuda.empty_cache()
+            except Exception as exc:  # an extra workload must not take the headline down with it
+                extra.append({"workload": name, "error": repr(exc)})
+        result["other_workloads"] = extra
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
