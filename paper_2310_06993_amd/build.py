@@ -21,6 +21,7 @@ CLASSES = (0, 11, 12, 13, 14, 15, 16)
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+FLAGS += os.environ.get("OR_HIPCC_EXTRA", "").split()   # e.g. -DOR_SWAP_STAGES=1 when trying a variant
 
 
 def _compile(job):

@@ -21,20 +21,25 @@ struct PathArgs {
   float scale;             // 2^(-k/2) rounded to fp32
 };
 
+// In the shard kernels a tile can be cut short only when blocks are smaller than a tile (class 0).
+template <int K> constexpr bool kShardTilesFull = (K != 0);
+// LDS buffers for the exchange: two (one barrier per exchange) while they fit several workgroups per CU.
+template <int K> constexpr int kXbufs = (Geo<K>::Q == 0) ? 0 : (Geo<K>::T * 4 <= 16384 ? 2 : 1);
+
 // +1/-1 entry of H_{2^HB}: row `part`, column q
 __device__ __forceinline__ float part_coef(int part, int q) { return (__builtin_popcount(part & q) & 1) ? -1.0f : 1.0f; }
 
 template <int K>
 __device__ __forceinline__ int tile_bits(int k) { return K ? Geo<K>::KT : k; }
 
-// Signed (and, for blocks above 2^14, +-combined) raw tile of one worker in layout A.
-template <int K, class In>
-__device__ __forceinline__ void load_signed_tile(const In* __restrict__ x, u64 limit, u64 unit, u64 seed, u64 base,
-                                                 int wave, int lane, float (&v)[R], const u64 (&sg_one)[R]) {
-  constexpr int T = Geo<K>::T, HB = Geo<K>::HB, PARTS = Geo<K>::PARTS;
+// Raw tile(s) of one worker in layout A, before signs.  For blocks above 2^14 the +-1 combination of
+// the block's tiles that feeds output tile `unit` is formed here, signs applied per input tile.
+template <int K, bool FULL, class In>
+__device__ __forceinline__ void load_raw_tile(const In* __restrict__ x, u64 limit, u64 unit, u64 seed, u64 base,
+                                              int wave, int lane, float (&v)[Geo<K>::R]) {
+  constexpr int T = Geo<K>::T, HB = Geo<K>::HB, PARTS = Geo<K>::PARTS, R = Geo<K>::R;
   if constexpr (PARTS == 1) {
-    load_tile<K, false>(x, unit * T, limit, wave, lane, v);
-    apply_signs(v, sg_one);
+    load_tile<K, false, FULL>(x, unit * T, limit, wave, lane, v);
   } else {
     const u64 blk = unit >> HB;
     const int part = (int)(unit & (PARTS - 1));
@@ -44,8 +49,8 @@ __device__ __forceinline__ void load_signed_tile(const In* __restrict__ x, u64 l
       const u64 tq = (blk << HB) + q;
       float t[R];
       u64 sg[R];
-      load_tile<K, false>(x, tq * T, limit, wave, lane, t);
-      sign_masks(seed, base + tq * T + (u64)wave * 1024, sg);
+      load_tile<K, false, FULL>(x, tq * T, limit, wave, lane, t);
+      sign_masks(seed, base + tq * T + (u64)wave * Geo<K>::WAVE_ENTRIES, sg);
       apply_signs(t, sg);
       const float c = part_coef(part, q);
 #pragma unroll
@@ -57,30 +62,34 @@ __device__ __forceinline__ void load_signed_tile(const In* __restrict__ x, u64 l
 // Sec. 3.3 encode: out = B^(-1/2) H D x, blockwise; pad of the last block is zero.
 template <int K, class In, class Wire>
 __global__ __launch_bounds__(Geo<K>::THREADS) void k_encode(PathArgs a) {
-  constexpr int T = Geo<K>::T;
+  constexpr int T = Geo<K>::T, R = Geo<K>::R;
   __shared__ float xbuf[Geo<K>::Q > 0 ? T : 1];
   const int wave = wave_id(), lane = lane_id(), kt = tile_bits<K>(a.k);
   const u64 unit = blockIdx.x;
   float v[R];
-  u64 sg[R];
-  if constexpr (Geo<K>::PARTS == 1) sign_masks(a.seed, a.base + unit * T + (u64)wave * 1024, sg);
-  load_signed_tile<K>((const In*)a.in, a.n, unit, a.seed, a.base, wave, lane, v, sg);
-  transform_a_to_b<K>(v, xbuf, wave, lane, kt);
+  load_raw_tile<K, false>((const In*)a.in, a.n, unit, a.seed, a.base, wave, lane, v);
+  if constexpr (Geo<K>::PARTS == 1) {
+    u64 sg[R];
+    sign_masks(a.seed, a.base + unit * T + (u64)wave * Geo<K>::WAVE_ENTRIES, sg);
+    apply_signs(v, sg);
+  }
+  transform<K, true>(v, xbuf, wave, lane, kt);
   const float c = a.scale * lane_sigma(lane, kt < 6 ? kt : 6);
 #pragma unroll
   for (int r = 0; r < R; ++r) v[r] *= c;
-  store_tile<K, true>((Wire*)a.out, unit * T, a.n_pad, wave, lane, v);
+  store_tile<K, true, false>((Wire*)a.out, unit * T, a.n_pad, wave, lane, v);
 }
 
 // Mean tile (layout B) for decode: either the mean itself, or sum / count with 0 where count is 0
 // (the "averages" of Sec. 3.1.1 taken over the entries that arrived).
 template <int K, bool FINALIZE>
-__device__ __forceinline__ void load_mean_tile(const PathArgs& a, u64 tile, int wave, int lane, float (&v)[R]) {
-  constexpr int T = Geo<K>::T;
-  load_tile<K, true>((const float*)a.in, tile * T, a.n_pad, wave, lane, v);
+__device__ __forceinline__ void load_mean_tile(const PathArgs& a, u64 tile, int wave, int lane,
+                                               float (&v)[Geo<K>::R]) {
+  constexpr int T = Geo<K>::T, R = Geo<K>::R;
+  load_tile<K, true, false>((const float*)a.in, tile * T, a.n_pad, wave, lane, v);
   if constexpr (FINALIZE) {
     float c[R];
-    load_tile<K, true>(a.count_in, tile * T, a.n_pad, wave, lane, c);
+    load_tile<K, true, false>(a.count_in, tile * T, a.n_pad, wave, lane, c);
 #pragma unroll
     for (int r = 0; r < R; ++r) v[r] = c[r] > 0.0f ? v[r] / c[r] : 0.0f;
   }
@@ -89,7 +98,7 @@ __device__ __forceinline__ void load_mean_tile(const PathArgs& a, u64 tile, int 
 // Sec. 3.3 / Sec. 4 decode: out = D B^(-1/2) H mean, first n entries kept.
 template <int K, class Out, bool FINALIZE>
 __global__ __launch_bounds__(Geo<K>::THREADS) void k_decode(PathArgs a) {
-  constexpr int T = Geo<K>::T, HB = Geo<K>::HB, PARTS = Geo<K>::PARTS;
+  constexpr int T = Geo<K>::T, HB = Geo<K>::HB, PARTS = Geo<K>::PARTS, R = Geo<K>::R;
   __shared__ float xbuf[Geo<K>::Q > 0 ? T : 1];
   const int wave = wave_id(), lane = lane_id(), kt = tile_bits<K>(a.k);
   const u64 unit = blockIdx.x;
@@ -109,131 +118,193 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_decode(PathArgs a) {
       for (int r = 0; r < R; ++r) v[r] = __builtin_fmaf(c, t[r], v[r]);
     }
   }
-  transform_b_to_a<K>(v, xbuf, wave, lane, kt);
+  transform<K, false>(v, xbuf, wave, lane, kt);
   const float c = a.scale * lane_sigma(lane, kt < 6 ? kt : 6);
   u64 sg[R];
-  sign_masks(a.seed, a.base + unit * T + (u64)wave * 1024, sg);
+  sign_masks(a.seed, a.base + unit * T + (u64)wave * Geo<K>::WAVE_ENTRIES, sg);
 #pragma unroll
   for (int r = 0; r < R; ++r) v[r] *= c;
   apply_signs(v, sg);
-  store_tile<K, false>((Out*)a.out, unit * T, a.n, wave, lane, v);
+  store_tile<K, false, false>((Out*)a.out, unit * T, a.n, wave, lane, v);
 }
 
-// acc += value where the worker's copy arrived; count of arrivals per entry = full + cnt.
-__device__ __forceinline__ void masked_accumulate(const float (&v)[R], const u64 (&m)[R], float (&acc)[R],
-                                                  int (&cnt)[R], int& full) {
-  u64 all = m[0];
+// acc += value where the worker's copy arrived.  Arrivals are counted as `full` (workers whose whole
+// tile part arrived) plus a per-register byte in cntp (four registers per word; N <= 255 keeps a byte
+// from overflowing).  `words` holds the worker's received bits as loaded by load_mask_words.
+template <int NR>
+__device__ __forceinline__ void masked_accumulate(const float (&v)[NR], uint32_t words, float (&acc)[NR],
+                                                  uint32_t (&cntp)[NR / 4], int& full) {
+  if (all_arrived(words)) {
 #pragma unroll
-  for (int r = 1; r < R; ++r) all &= m[r];
-  if (all == ~0ull) {
-#pragma unroll
-    for (int r = 0; r < R; ++r) acc[r] += v[r];
+    for (int r = 0; r < NR; ++r) acc[r] += v[r];
     ++full;
   } else {
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      const bool got = in_mask(m[r]);
+    for (int r = 0; r < NR; ++r) {
+      const bool got = in_mask(mask_of_reg(words, r));
       acc[r] += got ? v[r] : 0.0f;
-      cnt[r] += got ? 1 : 0;
+      cntp[r >> 2] += got ? (1u << (8 * (r & 3))) : 0u;
     }
   }
 }
 
-template <int K>
+template <int NR>
+__device__ __forceinline__ int count_of(const uint32_t (&cntp)[NR / 4], int full, int r) {
+  return (int)((cntp[r >> 2] >> (8 * (r & 3))) & 0xFFu) + full;
+}
+
+template <int K, bool FULL>
 __device__ __forceinline__ void store_counts(uint8_t* count_out, u64 e0, u64 limit, int wave, int lane,
-                                             const int (&cnt)[R], int full) {
+                                             const uint32_t (&cntp)[Geo<K>::R / 4], int full) {
+  constexpr int R = Geo<K>::R;
   if (!count_out) return;
 #pragma unroll
   for (int r = 0; r < R; ++r) {
-    u64 e = e0 + off_b<K>(wave, r) + lane;
-    if (e < limit) count_out[e] = (uint8_t)(cnt[r] + full);
+    const uint8_t c = (uint8_t)count_of<R>(cntp, full, r);
+    if (FULL) {
+      store_one<true>(&(count_out + e0 + off_b<K>(wave, r))[(unsigned)lane], c);
+    } else {
+      const u64 e = e0 + off_b<K>(wave, r) + lane;
+      if (e < limit) store_one<true>(count_out + e, c);
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+// mean over what arrived (0 where nothing arrived), times `post`.  The reciprocal of the count comes
+// from v_rcp_f32 (1 ulp), far inside the 1e-6 budget of the path.
+template <int NR>
+__device__ __forceinline__ void finalize_mean(float (&acc)[NR], const uint32_t (&cntp)[NR / 4], int full, float post) {
+  uint32_t any = 0;
+#pragma unroll
+  for (int r = 0; r < NR / 4; ++r) any |= cntp[r];
+  if (__builtin_amdgcn_ballot_w64(any != 0) == 0 && full > 0) {
+    const float f = post * __builtin_amdgcn_rcpf((float)full);   // every entry arrived `full` times
+#pragma unroll
+    for (int r = 0; r < NR; ++r) acc[r] *= f;
+  } else {
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+      const int c = count_of<NR>(cntp, full, r);
+      acc[r] = c ? acc[r] * (post * __builtin_amdgcn_rcpf((float)c)) : 0.0f;
+    }
   }
 }
 
 // Aggregation of N encoded shards (Sec. 3.1.1), mean over what arrived, decode (Sec. 3.3).  K <= 14.
+// The next worker's tile is in flight while the current one is accumulated.
 template <int K, class Wire, class Out>
 __global__ __launch_bounds__(Geo<K>::THREADS) void k_reduce_decode(PathArgs a) {
-  constexpr int T = Geo<K>::T;
+  constexpr int T = Geo<K>::T, R = Geo<K>::R;
+  constexpr bool FULL = kShardTilesFull<K>;
   static_assert(Geo<K>::PARTS == 1, "blocks above 2^14 go through sum/count in memory");
   __shared__ float xbuf[Geo<K>::Q > 0 ? T : 1];
   const int wave = wave_id(), lane = lane_id(), kt = tile_bits<K>(a.k);
-  const u64 unit = blockIdx.x, L = a.n_pad;
-  float acc[R];
-  int cnt[R], full = 0;
+  const u64 unit = blockIdx.x, L = a.n_pad, e0 = unit * T;
+  const Wire* shards = (const Wire*)a.in;
+  float acc[R], va[R], vb[R];
+  uint32_t ma, mb = 0, cnt[R / 4];
+  int full = 0;
+  const int moff = mask_word_offset<K>(wave, lane);
+  const u64 mrow = L >> 5;
 #pragma unroll
-  for (int r = 0; r < R; ++r) { acc[r] = 0.0f; cnt[r] = 0; }
-  for (int i = 0; i < a.N; ++i) {
-    float v[R];
-    u64 m[R];
-    load_tile<K, true>((const Wire*)a.in + (u64)i * L, unit * T, L, wave, lane, v);
-    load_masks<K>(a.masks + (u64)i * (L >> 5), unit * T, L, wave, m);
-    masked_accumulate(v, m, acc, cnt, full);
-  }
-  store_counts<K>(a.count_out, unit * T, L, wave, lane, cnt, full);
+  for (int r = 0; r < R; ++r) acc[r] = 0.0f;
 #pragma unroll
-  for (int r = 0; r < R; ++r) {
-    const int c = cnt[r] + full;
-    acc[r] = c ? acc[r] / (float)c : 0.0f;
+  for (int r = 0; r < R / 4; ++r) cnt[r] = 0;
+  load_tile<K, true, FULL>(shards, e0, L, wave, lane, va);
+  ma = load_mask_words<K, FULL>(a.masks, e0, L, moff);
+  for (int i = 0; i < a.N; i += 2) {
+    if (i + 1 < a.N) {
+      load_tile<K, true, FULL>(shards + (u64)(i + 1) * L, e0, L, wave, lane, vb);
+      mb = load_mask_words<K, FULL>(a.masks + (u64)(i + 1) * mrow, e0, L, moff);
+    }
+    masked_accumulate(va, ma, acc, cnt, full);
+    if (i + 1 < a.N) {
+      if (i + 2 < a.N) {
+        load_tile<K, true, FULL>(shards + (u64)(i + 2) * L, e0, L, wave, lane, va);
+        ma = load_mask_words<K, FULL>(a.masks + (u64)(i + 2) * mrow, e0, L, moff);
+      }
+      masked_accumulate(vb, mb, acc, cnt, full);
+    }
   }
-  transform_b_to_a<K>(acc, xbuf, wave, lane, kt);
+  store_counts<K, FULL>(a.count_out, e0, L, wave, lane, cnt, full);
+  finalize_mean(acc, cnt, full, 1.0f);
+  transform<K, false>(acc, xbuf, wave, lane, kt);
   const float c = a.scale * lane_sigma(lane, kt < 6 ? kt : 6);
   u64 sg[R];
-  sign_masks(a.seed, a.base + unit * T + (u64)wave * 1024, sg);
+  sign_masks(a.seed, a.base + e0 + (u64)wave * Geo<K>::WAVE_ENTRIES, sg);
 #pragma unroll
   for (int r = 0; r < R; ++r) acc[r] *= c;
   apply_signs(acc, sg);
-  store_tile<K, false>((Out*)a.out, unit * T, L, wave, lane, acc);
+  store_tile<K, false, FULL, true>((Out*)a.out, e0, L, wave, lane, acc);
 }
 
 // The whole path for one shard held by one node: the raw slices of N workers are encoded, the
 // encoded entries that arrived are summed and counted, the mean is decoded.  The encoded value is
 // rounded to the wire type (identity for fp32) before it is summed, so the result is the one the
 // three separate calls give.  DECODE = false (blocks above 2^14) stops at the fp32 mean.
+//
+// Per worker: sign flip (layout A), transform to layout B, round, add under the received mask.
+// No register prefetch of the next worker's tile: measured on MI355X, keeping the kernel small enough
+// for several independent workgroups per CU hides the load latency better than a second tile buffer.
 template <int K, class In, bool DECODE>
-__global__ __launch_bounds__(Geo<K>::THREADS) void k_fused(PathArgs a) {
-  constexpr int T = Geo<K>::T;
+__global__ __launch_bounds__(Geo<K>::THREADS) __attribute__((amdgpu_waves_per_eu(Geo<K>::R == 32 ? 4 : 1)))
+void k_fused(PathArgs a) {
+  constexpr int T = Geo<K>::T, NB = kXbufs<K>, R = Geo<K>::R;
+  constexpr bool FULL = kShardTilesFull<K>;
   static_assert(DECODE == (Geo<K>::PARTS == 1), "decode in the same kernel only when a block is one tile");
-  __shared__ float xbuf[Geo<K>::Q > 0 ? T : 1];
+  __shared__ float xbuf[NB ? NB : 1][NB ? T : 1];
   const int wave = wave_id(), lane = lane_id(), kt = tile_bits<K>(a.k);
-  const u64 unit = blockIdx.x, L = a.n_pad;
+  const u64 unit = blockIdx.x, L = a.n_pad, e0 = unit * T;
+  const In* grads = (const In*)a.in;
   const float sigma = lane_sigma(lane, kt < 6 ? kt : 6);
   // a power-of-two scale commutes with rounding to the wire type; any other scale is applied first
   const bool scale_first = sizeof(In) == 2 && (a.k & 1);
   u64 sg[R];
-  if constexpr (Geo<K>::PARTS == 1) sign_masks(a.seed, a.base + unit * T + (u64)wave * 1024, sg);
-  float acc[R];
-  int cnt[R], full = 0;
+  if constexpr (Geo<K>::PARTS == 1) sign_masks(a.seed, a.base + e0 + (u64)wave * Geo<K>::WAVE_ENTRIES, sg);
+  float acc[R], va[R];
+  uint32_t cnt[R / 4];
+  int full = 0, flip = 0;
 #pragma unroll
-  for (int r = 0; r < R; ++r) { acc[r] = 0.0f; cnt[r] = 0; }
-  for (int i = 0; i < a.N; ++i) {
-    float v[R];
-    u64 m[R];
-    load_signed_tile<K>((const In*)a.in + (u64)i * L, L, unit, a.seed, a.base, wave, lane, v, sg);
-    transform_a_to_b<K>(v, xbuf, wave, lane, kt);
+  for (int r = 0; r < R; ++r) acc[r] = 0.0f;
+#pragma unroll
+  for (int r = 0; r < R / 4; ++r) cnt[r] = 0;
+
+  const int moff = mask_word_offset<K>(wave, lane);
+  const u64 mrow = L >> 5;
+  uint32_t ma;
+
+  auto step = [&](float (&v)[R], uint32_t m) {
+    if constexpr (Geo<K>::PARTS == 1) apply_signs(v, sg);
+    transform<K, true, NB != 2>(v, xbuf[NB == 2 ? flip : 0], wave, lane, kt);
+    flip ^= 1;
     if (sizeof(In) == 2) {
       const float pre = scale_first ? a.scale : 1.0f;
 #pragma unroll
       for (int r = 0; r < R; ++r) v[r] = round_to<In>(v[r] * pre);
     }
-    load_masks<K>(a.masks + (u64)i * (L >> 5), unit * T, L, wave, m);
     masked_accumulate(v, m, acc, cnt, full);
+  };
+
+  for (int i = 0; i < a.N; ++i) {
+    load_raw_tile<K, FULL>(grads + (u64)i * L, L, unit, a.seed, a.base, wave, lane, va);
+    ma = load_mask_words<K, FULL>(a.masks + (u64)i * mrow, e0, L, moff);
+    step(va, ma);
   }
-  store_counts<K>(a.count_out, unit * T, L, wave, lane, cnt, full);
-  const float post = sigma * (scale_first ? 1.0f : a.scale);
-#pragma unroll
-  for (int r = 0; r < R; ++r) {
-    const int c = cnt[r] + full;
-    acc[r] = c ? acc[r] * post / (float)c : 0.0f;
-  }
+  __builtin_amdgcn_sched_barrier(0);
+  store_counts<K, FULL>(a.count_out, e0, L, wave, lane, cnt, full);
+  finalize_mean(acc, cnt, full, sigma * (scale_first ? 1.0f : a.scale));
+  __builtin_amdgcn_sched_barrier(0);
   if constexpr (DECODE) {
-    transform_b_to_a<K>(acc, xbuf, wave, lane, kt);
+    transform<K, false, NB != 2>(acc, xbuf[NB == 2 ? flip : 0], wave, lane, kt);
+    __builtin_amdgcn_sched_barrier(0);
     const float c = a.scale * sigma;
 #pragma unroll
     for (int r = 0; r < R; ++r) acc[r] *= c;
     apply_signs(acc, sg);
-    store_tile<K, false>((In*)a.out, unit * T, L, wave, lane, acc);
+    store_tile<K, false, FULL, true>((In*)a.out, e0, L, wave, lane, acc);
   } else {
-    store_tile<K, true>(a.mean_out, unit * T, L, wave, lane, acc);
+    store_tile<K, true, FULL>(a.mean_out, e0, L, wave, lane, acc);
   }
 }
 
