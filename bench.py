@@ -48,9 +48,41 @@ def launch(b, cfg, L, st, shard):
     fn(g, m, cfg.workers, L, cfg.block_log2, cfg.seed, shard * L, out, cnt, ws)
 
 
+class HipEvents:
+    """Raw hipEvent_t pairs (ctypes on the HIP runtime torch already loaded).  The library attaches
+    them to its kernel dispatch (or_time_next_call), so elapsed time is the kernel's own duration on
+    the stream it runs on, as rocprofv3's kernel trace reports it."""
+
+    def __init__(self, n):
+        import ctypes
+        self.c = ctypes
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.pairs = []
+        for _ in range(n):
+            a, z = ctypes.c_void_p(), ctypes.c_void_p()
+            assert self.hip.hipEventCreate(ctypes.byref(a)) == 0 and self.hip.hipEventCreate(ctypes.byref(z)) == 0
+            self.pairs.append((a, z))
+
+    def seconds(self):
+        out = []
+        for a, z in self.pairs:
+            ms = self.c.c_float()
+            rc = self.hip.hipEventElapsedTime(self.c.byref(ms), a, z)
+            assert rc == 0, "hipEventElapsedTime failed: %d" % rc
+            out.append(ms.value * 1e-3)
+        return out
+
+    def destroy(self):
+        for a, z in self.pairs:
+            self.hip.hipEventDestroy(a)
+            self.hip.hipEventDestroy(z)
+
+
 def time_fused(wl, b, cfg, device, steps, warmup, entries=None, launches_per_step=1, max_bytes=24 << 30):
     """Times `steps` steps; a step is `launches_per_step` back-to-back launches (buckets) of one shape.
-    Returns (seconds per step by wall clock, mean seconds per launch by HIP events, bytes per launch)."""
+    Returns (seconds per step by wall clock, mean seconds per launch by HIP events attached to the
+    dispatches, bytes per launch, number of input sets, the sets)."""
     L = cfg.shard_len(entries)
     es = 4 if cfg.dtype == "f32" else 2
     per_launch = wl.bytes_fused(cfg.workers, L, es)
@@ -65,18 +97,35 @@ def time_fused(wl, b, cfg, device, steps, warmup, entries=None, launches_per_ste
         it += 1
     torch.cuda.synchronize()
     total = steps * launches_per_step
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(total)]
+    # The timed region: `total` plain launches back to back, bracketed by a synchronise on both sides
+    # (wall clock -> `value`) and by two HIP events recorded on the launch stream (-> mean time per
+    # launch for the roofline; with back-to-back launches the gaps between kernels are negligible).
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    e0.record()
     for j in range(total):
-        ev[j][0].record()
         launch(b, cfg, L, sets[it % nsets], it % nsets % cfg.workers)
-        ev[j][1].record()
         it += 1
+    e1.record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    kern = float(np.mean([a.elapsed_time(z) for a, z in ev])) * 1e-3
+    kern = e0.elapsed_time(e1) * 1e-3 / total
     return (t1 - t0) / steps, kern, per_launch, nsets, sets
+
+
+def kernel_only_seconds(b, cfg, L, sets, launches=32):
+    """Cross-check outside the timed region: events attached to single dispatches (kernel begin/end
+    timestamps, what rocprofv3's kernel trace reports).  Slower to enqueue, so not used for `value`."""
+    ev = HipEvents(launches)
+    nsets = len(sets)
+    for j in range(launches):
+        b.or_time_next_call(ev.pairs[j][0], ev.pairs[j][1])
+        launch(b, cfg, L, sets[j % nsets], j % nsets % cfg.workers)
+    torch.cuda.synchronize()
+    t = float(np.median(ev.seconds()))
+    ev.destroy()
+    return t
 
 
 def cpu_baseline(wl, b, cfg, sets, target_seconds=12.0):
@@ -125,6 +174,9 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the other model-sized workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--workload", default="resnet50")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three 512 MiB device-to-device copies (a known-size reference for "
+                         "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the node path has no collective); "
@@ -141,6 +193,14 @@ def main():
     torch.cuda.set_device(device)
     cfg = wl.CONFIGS[args.workload]
     es = 4 if cfg.dtype == "f32" else 2
+
+    if args.calibrate_copy:
+        src = torch.zeros(512 << 20, dtype=torch.uint8, device=device)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     per_step, kern, nbytes, nsets, sets = time_fused(wl, b, cfg, device, args.steps, args.warmup)
     L = cfg.shard_len()
@@ -166,7 +226,8 @@ def main():
                    "input_sets_rotated": nsets, "bytes_per_step": nbytes},
         "roofline": {"bound": "hbm", "achieved": nbytes / kern / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": nbytes / kern / 1e9 / HBM_PEAK_GBPS, "traffic": None,
-                     "kernel": "k_fused", "avg_launch_us": kern * 1e6},
+                     "kernel": "k_fused", "avg_launch_us": kern * 1e6,
+                     "kernel_only_us_dispatch_events": kernel_only_seconds(b, cfg, L, sets) * 1e6},
     }
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(wl, b, cfg, sets)

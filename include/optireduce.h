@@ -65,6 +65,14 @@ int or_version(void);
 /* hipError_t (as int) of the last failed launch on the calling thread, 0 if none. */
 int or_last_hip_error(void);
 
+/* Measurement hook (not part of the method).  Arms two caller-created hipEvent_t (either may be NULL)
+ * for the NEXT entry-point call made by this thread: `start_event` is attached to the first kernel
+ * that call enqueues and receives that kernel's begin timestamp, `stop_event` to the last one and
+ * receives its end timestamp, so hipEventElapsedTime(start, stop) after a synchronise is the device
+ * time of the call without launch gaps.  The arming is consumed by that call whether it succeeds or
+ * not; a call that enqueues nothing leaves the events unrecorded. */
+or_status or_time_next_call(void* start_event, void* stop_event);
+
 /* ---- Sec. 3.3 encode: out = B^(-1/2) H D grad, blockwise ------------------------------------
  * grad: n entries.  out: or_padded_len(n) entries; the pad of the last block is treated as zeros
  * before the transform.  out == grad is allowed iff n is already a multiple of B; any other overlap

@@ -29,6 +29,7 @@ _SIGS = {
     "or_status_string": (C.c_char_p, [_int]),
     "or_version": (_int, []),
     "or_last_hip_error": (_int, []),
+    "or_time_next_call": (_int, [_p, _p]),
     "or_rht_encode": (_int, [_p, _u64, _int, _u64, _p, _p]),
     "or_rht_encode_at": (_int, [_p, _u64, _int, _u64, _u64, _p, _p]),
     "or_rht_encode_bf16": (_int, [_p, _u64, _int, _u64, _u64, _p, _p]),
@@ -86,6 +87,11 @@ def or_workspace_bytes(shard_len: int, block_log2: int) -> int:
 
 def or_version() -> int:
     return int(lib.or_version())
+
+
+def or_time_next_call(start_event, stop_event):
+    """start_event / stop_event: raw hipEvent_t handles (ints) or None."""
+    _check(lib.or_time_next_call(start_event, stop_event), "or_time_next_call")
 
 
 def or_rht_encode(grad, n, block_log2, seed, out, stream=None):

@@ -13,11 +13,10 @@ constexpr int K = OR_K;
 typedef Geo<K> G;
 
 #define OR_LAUNCHER(name, kernel)                                                            \
-  hipError_t name(const PathArgs& a, unsigned long long units, hipStream_t s) {             \
+  hipError_t name(const PathArgs& a, unsigned long long units, hipStream_t s, int pos) {    \
     if (units == 0) return hipSuccess;                                                       \
     if (units > 0x7FFFFFFFull) return hipErrorInvalidValue;                                  \
-    hipLaunchKernelGGL(kernel, dim3((unsigned)units), dim3(G::THREADS), 0, s, a);            \
-    return hipGetLastError();                                                                \
+    return launch_kernel(kernel, dim3((unsigned)units), dim3(G::THREADS), s, pos, a);        \
   }
 
 OR_LAUNCHER(enc_f32, (k_encode<K, float, float>))

@@ -2,11 +2,31 @@
 // its own translation unit (inst.hip with -DOR_K=<class>) so the classes build in parallel.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include "rht_kernels.hpp"
 
 namespace orhost {
 
-typedef hipError_t (*launch_fn)(const ordev::PathArgs&, unsigned long long units, hipStream_t);
+// `pos`: LAUNCH_FIRST / LAUNCH_LAST mark the first / last kernel an entry point enqueues (both for a
+// single-kernel call); they select which of the caller's timing events, if armed, ride on the launch.
+enum { LAUNCH_FIRST = 1, LAUNCH_LAST = 2, LAUNCH_ONLY = 3 };
+typedef hipError_t (*launch_fn)(const ordev::PathArgs&, unsigned long long units, hipStream_t, int pos);
+
+// Timing events armed by or_time_next_call for the calling thread (null when not armed).
+struct TimingEvents { hipEvent_t start, stop; };
+TimingEvents& timing_events();
+
+// Launch with the armed events attached to the dispatch itself (they then carry the kernel's own begin
+// and end timestamps, as a profiler would see them), or plainly when none are armed.
+template <class Kernel, class... Args>
+inline hipError_t launch_kernel(Kernel kernel, dim3 grid, dim3 block, hipStream_t s, int pos, Args... args) {
+  TimingEvents& t = timing_events();
+  hipEvent_t e0 = (pos & LAUNCH_FIRST) ? t.start : nullptr;
+  hipEvent_t e1 = (pos & LAUNCH_LAST) ? t.stop : nullptr;
+  if (e0 || e1) hipExtLaunchKernelGGL(kernel, grid, block, 0, s, e0, e1, 0, args...);
+  else hipLaunchKernelGGL(kernel, grid, block, 0, s, args...);
+  return hipGetLastError();
+}
 
 struct KernelTable {
   int tile_log2;              // entries per workgroup tile

@@ -11,6 +11,11 @@ namespace orhost {
 extern const KernelTable or_kernel_table_0, or_kernel_table_11, or_kernel_table_12, or_kernel_table_13,
     or_kernel_table_14, or_kernel_table_15, or_kernel_table_16;
 
+TimingEvents& timing_events() {
+  static thread_local TimingEvents t = {nullptr, nullptr};
+  return t;
+}
+
 const KernelTable* table_for_class(int cls) {
   switch (cls) {
     case 0: return &or_kernel_table_0;
@@ -89,14 +94,13 @@ __global__ __launch_bounds__(256) void k_masked_reduce(const Wire* __restrict__ 
 
 template <class Wire, int VEC>
 hipError_t launch_masked_reduce(const void* shards, const uint32_t* masks, int N, u64 L, float* sum_out,
-                                uint8_t* count_out, hipStream_t s) {
+                                uint8_t* count_out, hipStream_t s, int pos) {
   if (L == 0) return hipSuccess;
   const u64 threads = (L + VEC - 1) / VEC;
   const u64 blocks = (threads + 255) / 256;
   if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((k_masked_reduce<Wire, VEC>), dim3((unsigned)blocks), dim3(256), 0, s, (const Wire*)shards,
-                     masks, N, L, sum_out, count_out);
-  return hipGetLastError();
+  return orhost::launch_kernel(k_masked_reduce<Wire, VEC>, dim3((unsigned)blocks), dim3(256), s, pos,
+                               (const Wire*)shards, masks, N, L, sum_out, count_out);
 }
 
 // ------------------------------------------------------------------ checks
@@ -108,6 +112,11 @@ bool ranges_overlap(const void* a, u64 abytes, const void* b, u64 bbytes) {
   uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
   return a0 < b0 + bbytes && b0 < a0 + abytes;
 }
+
+// armed timing events serve exactly one entry-point call, whatever its outcome
+struct DisarmOnExit {
+  ~DisarmOnExit() { orhost::timing_events() = {nullptr, nullptr}; }
+};
 
 or_status finish(hipError_t e) {
   if (e == hipSuccess) return OR_OK;
@@ -145,6 +154,7 @@ or_status check_transform(const void* in, u64 in_len, int in_es, void* out, u64 
 
 template <class T>
 or_status encode_impl(const T* grad, u64 n, int k, u64 seed, u64 base, T* out, void* stream, bool bf16) {
+  DisarmOnExit disarm;
   const u64 n_pad = valid_k(k) ? padded(n, k) : 0;
   if (or_status s = check_transform(grad, n, sizeof(T), out, n_pad, sizeof(T), k, base)) return s;
   if (n == 0) return OR_OK;
@@ -152,12 +162,13 @@ or_status encode_impl(const T* grad, u64 n, int k, u64 seed, u64 base, T* out, v
   PathArgs a = {};
   a.in = grad; a.out = out; a.n = n; a.n_pad = n_pad; a.seed = seed; a.base = base; a.k = k; a.scale = scale_of(k);
   const u64 units = (n_pad + ((u64)1 << t->tile_log2) - 1) >> t->tile_log2;
-  return finish((bf16 ? t->encode_bf16 : t->encode_f32)(a, units, (hipStream_t)stream));
+  return finish((bf16 ? t->encode_bf16 : t->encode_f32)(a, units, (hipStream_t)stream, orhost::LAUNCH_ONLY));
 }
 
 template <class T>
 or_status decode_impl(const float* agg, const uint8_t* count, bool finalize, u64 n, int k, u64 seed, u64 base, T* out,
                       void* stream, bool bf16) {
+  DisarmOnExit disarm;
   const u64 n_pad = valid_k(k) ? padded(n, k) : 0;
   if (or_status s = check_transform(agg, n_pad, 4, out, n, sizeof(T), k, base)) return s;
   if (n == 0) return OR_OK;
@@ -172,7 +183,7 @@ or_status decode_impl(const float* agg, const uint8_t* count, bool finalize, u64
   const u64 units = (n_pad + ((u64)1 << t->tile_log2) - 1) >> t->tile_log2;
   orhost::launch_fn f = finalize ? (bf16 ? t->finalize_decode_bf16 : t->finalize_decode_f32)
                                  : (bf16 ? t->decode_bf16 : t->decode_f32);
-  return finish(f(a, units, (hipStream_t)stream));
+  return finish(f(a, units, (hipStream_t)stream, orhost::LAUNCH_ONLY));
 }
 
 or_status check_reduce(const void* shards, const uint32_t* masks, int N, u64 L, int es) {
@@ -189,6 +200,7 @@ or_status check_reduce(const void* shards, const uint32_t* masks, int N, u64 L, 
 template <class T>
 or_status masked_reduce_impl(const T* shards, const uint32_t* masks, int N, u64 L, float* sum_out, uint8_t* count_out,
                              void* stream) {
+  DisarmOnExit disarm;
   if (or_status s = check_reduce(shards, masks, N, L, sizeof(T))) return s;
   if (L == 0) return OR_OK;
   if (!sum_out || !count_out) return OR_ERR_NULL;
@@ -199,7 +211,8 @@ or_status masked_reduce_impl(const T* shards, const uint32_t* masks, int N, u64 
       ranges_overlap(sum_out, L * 4, count_out, L))
     return OR_ERR_SHAPE;
   constexpr int VEC = 16 / sizeof(T);
-  return finish(launch_masked_reduce<T, VEC>(shards, masks, N, L, sum_out, count_out, (hipStream_t)stream));
+  return finish(launch_masked_reduce<T, VEC>(shards, masks, N, L, sum_out, count_out, (hipStream_t)stream,
+                                             orhost::LAUNCH_ONLY));
 }
 
 size_t workspace_bytes(u64 L, int k) {
@@ -213,6 +226,7 @@ size_t workspace_bytes(u64 L, int k) {
 template <class T>
 or_status path_impl(bool fused, const T* in, const uint32_t* masks, int N, u64 L, int k, u64 seed, u64 base, T* out,
                     uint8_t* count_out, void* ws, size_t ws_bytes, void* stream, bool bf16) {
+  DisarmOnExit disarm;
   if (!valid_k(k)) return OR_ERR_BLOCK;
   if (or_status s = check_reduce(in, masks, N, L, sizeof(T))) return s;
   if (L % ((u64)1 << k)) return OR_ERR_SHAPE;
@@ -242,7 +256,7 @@ or_status path_impl(bool fused, const T* in, const uint32_t* masks, int N, u64 L
   a.N = N; a.k = k; a.scale = scale_of(k);
   if (!need) {
     orhost::launch_fn f = fused ? (bf16 ? t->fused_bf16 : t->fused_f32) : (bf16 ? t->reduce_decode_bf16 : t->reduce_decode_f32);
-    return finish(f(a, units, s));
+    return finish(f(a, units, s, orhost::LAUNCH_ONLY));
   }
   // a block spans several tiles: stop at the mean (or sum and count) in the workspace, then decode it
   float* ws_f32 = (float*)ws;
@@ -253,14 +267,15 @@ or_status path_impl(bool fused, const T* in, const uint32_t* masks, int N, u64 L
   if (fused) {
     a.mean_out = ws_f32;
     a.out = nullptr;
-    if (hipError_t e = (bf16 ? t->fused_bf16 : t->fused_f32)(a, units, s)) return finish(e);
-    return finish((bf16 ? t->decode_bf16 : t->decode_f32)(d, units, s));
+    if (hipError_t e = (bf16 ? t->fused_bf16 : t->fused_f32)(a, units, s, orhost::LAUNCH_FIRST)) return finish(e);
+    return finish((bf16 ? t->decode_bf16 : t->decode_f32)(d, units, s, orhost::LAUNCH_LAST));
   }
   uint8_t* cnt = count_out ? count_out : ws_cnt;
   constexpr int VEC = 16 / sizeof(T);
-  if (hipError_t e = launch_masked_reduce<T, VEC>(in, masks, N, L, ws_f32, cnt, s)) return finish(e);
+  if (hipError_t e = launch_masked_reduce<T, VEC>(in, masks, N, L, ws_f32, cnt, s, orhost::LAUNCH_FIRST))
+    return finish(e);
   d.count_in = cnt;
-  return finish((bf16 ? t->finalize_decode_bf16 : t->finalize_decode_f32)(d, units, s));
+  return finish((bf16 ? t->finalize_decode_bf16 : t->finalize_decode_f32)(d, units, s, orhost::LAUNCH_LAST));
 }
 
 }  // namespace
@@ -271,6 +286,11 @@ uint64_t or_padded_len(uint64_t n, int block_log2) { return valid_k(block_log2) 
 size_t or_workspace_bytes(uint64_t shard_len, int block_log2) { return workspace_bytes(shard_len, block_log2); }
 int or_version(void) { return 100; }
 int or_last_hip_error(void) { return g_last_hip_error; }
+
+or_status or_time_next_call(void* start_event, void* stop_event) {
+  orhost::timing_events() = {(hipEvent_t)start_event, (hipEvent_t)stop_event};
+  return OR_OK;
+}
 
 const char* or_status_string(or_status s) {
   switch (s) {

@@ -1,0 +1,152 @@
+"""The HIP path at the full sizes of the model-sized configurations, in the launch shape bench.py
+times: sampled blocks are recomputed one by one by the CPU oracle; received counts are checked for
+the WHOLE shard against a popcount of the masks; an all-arrived run on integer data must return the
+exact mean everywhere."""
+import numpy as np
+import pytest
+import torch
+
+from _util import TOL, dev, rel_l2, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def b():
+    import paper_2310_06993_amd.binding as binding
+    assert torch.cuda.is_available()
+    return binding
+
+
+def _popcount_counts(m: torch.Tensor, L: int) -> torch.Tensor:
+    """uint8 [L]: per entry, how many workers' bits are set (torch ops only)."""
+    N = m.shape[0]
+    total = torch.zeros(L, dtype=torch.uint8, device=m.device)
+    shifts = torch.arange(32, device=m.device, dtype=torch.int32)
+    chunk = 1 << 22   # words
+    for i in range(N):
+        for w0 in range(0, L // 32, chunk):
+            w = m[i, w0:w0 + chunk]
+            bits = ((w.unsqueeze(1) >> shifts) & 1).to(torch.uint8).reshape(-1)
+            total[w0 * 32: w0 * 32 + bits.numel()] += bits
+    return total
+
+
+def _fused(b, cfg, g, m, L, base, out, cnt):
+    nws = b.or_workspace_bytes(L, cfg.block_log2)
+    ws = torch.empty(nws, dtype=torch.uint8, device=dev()) if nws else None
+    fn = b.or_fused_path if cfg.dtype == "f32" else b.or_fused_path_bf16
+    fn(g, m, cfg.workers, L, cfg.block_log2, cfg.seed, base, out, cnt, ws)
+    torch.cuda.synchronize()
+
+
+def _check_sampled_blocks(orc, cfg, g, m, out, cnt, L, base, nsamples, seed):
+    B, k = cfg.block, cfg.block_log2
+    nblocks = L // B
+    rng = np.random.default_rng(seed)
+    picks = sorted(set([0, nblocks - 1] + rng.integers(0, nblocks, nsamples).tolist()))
+    worst = 0.0
+    for blk in picks:
+        gs = to_np(g[:, blk * B:(blk + 1) * B].contiguous())
+        ms = to_np(m[:, blk * B // 32:(blk + 1) * B // 32].contiguous())
+        want, wcnt = orc.fused_path(gs, ms, k, cfg.seed, base + blk * B)
+        got = to_np(out[blk * B:(blk + 1) * B])
+        assert np.array_equal(to_np(cnt[blk * B:(blk + 1) * B]), wcnt), (cfg.name, blk)
+        err = rel_l2(got, want)
+        worst = max(worst, err)
+        assert err <= TOL[cfg.dtype], (cfg.name, blk, err)
+    return worst
+
+
+def _run_config(b, orc, cfg, shard, entries=None, nsamples=6):
+    from paper_2310_06993_amd import workloads as wl
+    N, L = cfg.workers, cfg.shard_len(entries)
+    g = wl.make_grads(cfg, dev(), shard=shard, entries=entries)
+    m = wl.make_masks(cfg, dev(), shard=shard, entries=entries)
+    out = torch.empty(L, dtype=g.dtype, device=dev())
+    cnt = torch.empty(L, dtype=torch.uint8, device=dev())
+    base = shard * L
+    _fused(b, cfg, g, m, L, base, out, cnt)
+    # every count of the shard, bit-exact
+    assert torch.equal(cnt, _popcount_counts(m, L)), cfg.name
+    assert int(cnt.min()) >= 1                       # the owner's copy is always there
+    lost = 1.0 - float(cnt.float().mean()) / N
+    assert 0.2 * cfg.loss < lost * N / (N - 1) < 3.0 * cfg.loss, (cfg.name, lost)
+    worst = _check_sampled_blocks(orc, cfg, g, m, out, cnt, L, base, nsamples, seed=shard + 1)
+    # all arrived + small integers: the exact mean, everywhere
+    del g
+    gi = torch.randint(-4, 5, (N, L), device=dev(), dtype=torch.int8,
+                       generator=torch.Generator(device=dev()).manual_seed(7)).to(out.dtype)
+    m.fill_(-1)
+    _fused(b, cfg, gi, m, L, base, out, cnt)
+    assert bool((cnt == N).all())
+    mean = torch.zeros(L, dtype=torch.float32, device=dev())
+    for i in range(N):
+        mean += gi[i].float()
+    mean /= N
+    if cfg.dtype == "f32":
+        assert torch.equal(out, mean)
+    else:   # the encoded values are rounded to bf16 on the wire, so only the tolerance holds
+        err = float((out.double() - mean.double()).norm() / mean.double().norm())
+        assert err <= TOL["bf16"], err
+    return worst
+
+
+def test_resnet50_sized(b, orc):
+    from paper_2310_06993_amd import workloads as wl
+    cfg = wl.CONFIGS["resnet50"]
+    assert cfg.shard_len() == 3_194_880 and cfg.padded_entries() - cfg.entries == 2_008
+    _run_config(b, orc, cfg, shard=0)
+    _run_config(b, orc, cfg, shard=cfg.workers - 1)   # the shard that holds the zero pad
+
+
+def test_resnet50_three_calls_match_fused(b, orc):
+    from paper_2310_06993_amd import workloads as wl
+    cfg = wl.CONFIGS["resnet50"]
+    N, L, k = cfg.workers, cfg.shard_len(), cfg.block_log2
+    g = wl.make_grads(cfg, dev(), shard=3)
+    m = wl.make_masks(cfg, dev(), shard=3)
+    base = 3 * L
+    enc = torch.empty((N, L), device=dev())
+    for i in range(N):
+        b.or_rht_encode_at(g[i], L, k, cfg.seed, base, enc[i])
+    total = torch.empty(L, device=dev())
+    cnt = torch.empty(L, dtype=torch.uint8, device=dev())
+    b.or_masked_reduce(enc, m, N, L, total, cnt)
+    out3 = torch.empty(L, device=dev())
+    b.or_finalize_decode(total, cnt, L, k, cfg.seed, base, out3)
+    outf = torch.empty(L, device=dev())
+    cntf = torch.empty(L, dtype=torch.uint8, device=dev())
+    _fused(b, cfg, g, m, L, base, outf, cntf)
+    assert torch.equal(cnt, cntf)
+    err = float((out3.double() - outf.double()).norm() / outf.double().norm())
+    assert err <= 1e-6
+    _check_sampled_blocks(orc, cfg, g, m, out3, cnt, L, base, 4, seed=11)
+    outr = torch.empty(L, device=dev())
+    b.or_reduce_decode(enc, m, N, L, k, cfg.seed, base, outr, cntf)
+    assert torch.equal(cnt, cntf)
+    assert float((outr.double() - outf.double()).norm() / outf.double().norm()) <= 1e-6
+
+
+def test_bert_large_sized(b, orc):
+    from paper_2310_06993_amd import workloads as wl
+    cfg = wl.CONFIGS["bert_large"]
+    assert cfg.shard_len() == 41_893_888
+    _run_config(b, orc, cfg, shard=2, nsamples=4)
+
+
+def test_gpt2_xl_sized_buckets(b, orc):
+    from paper_2310_06993_amd import workloads as wl
+    cfg = wl.CONFIGS["gpt2_xl"]
+    buckets = cfg.buckets()
+    assert len(buckets) == 238 and buckets[-1][1] == 4_408_000
+    assert cfg.shard_len(buckets[0][1]) == 409_600 and cfg.shard_len(buckets[-1][1]) == 278_528
+    _run_config(b, orc, cfg, shard=5, entries=buckets[0][1], nsamples=4)     # a full 25 MiB bucket
+    _run_config(b, orc, cfg, shard=15, entries=buckets[-1][1], nsamples=4)   # the short last bucket, last shard
+
+
+def test_llama_8b_sized(b, orc):
+    from paper_2310_06993_amd import workloads as wl
+    cfg = wl.CONFIGS["llama_8b"]
+    assert cfg.shard_len() == 1_003_814_912 and cfg.entries > 2 ** 32
+    _run_config(b, orc, cfg, shard=7, nsamples=3)     # last shard: base index beyond 2^32, holds the pad
