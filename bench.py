@@ -248,6 +248,26 @@ def main():
                     by_step = by * nb   # the short last bucket is counted as a full one: a few % high on bytes AND time
                     ent = c.workers * c.shard_len(c.bucket_entries) * nb
                     note = "%d back-to-back launches of one 25 MiB bucket shape per step" % nb
+                    extra.append({"workload": name + " (one launch per bucket)", "GB_per_s": by_step / ps / 1e9,
+                                  "entries_per_s": ent / ps, "ms_per_step": ps * 1e3, "avg_launch_us": kn * 1e6,
+                                  "launch_GB_per_s": by / kn / 1e9, "frac_hbm_peak": by / kn / 1e9 / HBM_PEAK_GBPS,
+                                  "input_sets_rotated": ns, "note": note})
+                    # the same buckets through the batched entry point: 32 buckets per launch
+                    Lb = c.shard_len(c.bucket_entries)
+                    arr = b.make_buckets([(st[j % ns][0], st[j % ns][1], st[j % ns][2], st[j % ns][3], Lb, c.seed,
+                                           (j % ns % c.workers) * Lb) for j in range(nb)])
+                    for _ in range(2):
+                        b.or_fused_path_batched(arr, nb, c.workers, c.block_log2, False)
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    for _ in range(steps):
+                        b.or_fused_path_batched(arr, nb, c.workers, c.block_log2, False)
+                    torch.cuda.synchronize()
+                    ps = (time.perf_counter() - t0) / steps
+                    kn = ps / -(-nb // 32)
+                    by = by_step / -(-nb // 32)
+                    note = "all %d buckets per step through or_fused_path_batched (%d launches)" % (nb, -(-nb // 32))
+                    name = name + " (batched)"
                 else:
                     ps, kn, by, ns, st = time_fused(wl, b, c, device, steps, 2)
                     by_step, ent, note = by, c.workers * c.shard_len(), "one launch per step"

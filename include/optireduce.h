@@ -135,6 +135,25 @@ or_status or_fused_path_bf16(const uint16_t* grads, const uint32_t* masks, int N
                              int block_log2, uint64_t seed, uint64_t base_index, uint16_t* out, uint8_t* count_out,
                              void* workspace, size_t workspace_bytes, void* stream);
 
+/* or_fused_path_batched: or_fused_path / or_fused_path_bf16 for several buckets that share N,
+ * block_log2 and element type, in as few launches as possible (up to 32 buckets per launch).  A DDP
+ * bucket (Sec. 3.1.1 footnote: 25 MB by default) is only about a hundred tiles per shard, far too few
+ * to fill the GPU alone.  `buckets` is a HOST array, read before the call returns; the device
+ * pointers in it follow the rules of or_fused_path (grads/out are float or bf16 bits per `bf16`).
+ * Every bucket is validated before anything is enqueued.  For block_log2 > 14 the buckets are run one
+ * after the other and `workspace` must cover the largest or_workspace_bytes() among them. */
+typedef struct or_bucket {
+  const void* grads;      /* [N][shard_len] raw slices                  */
+  const uint32_t* masks;  /* [N][shard_len/32]                          */
+  void* out;              /* shard_len entries                          */
+  uint8_t* count_out;     /* shard_len counts, or NULL                  */
+  uint64_t shard_len;
+  uint64_t seed;
+  uint64_t base_index;
+} or_bucket;
+or_status or_fused_path_batched(const or_bucket* buckets, int n_buckets, int N, int block_log2, int bf16,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

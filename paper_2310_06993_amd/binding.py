@@ -44,7 +44,13 @@ _SIGS = {
     "or_reduce_decode_bf16": (_int, [_p, _p, _int, _u64, _int, _u64, _u64, _p, _p, _p, _sz, _p]),
     "or_fused_path": (_int, [_p, _p, _int, _u64, _int, _u64, _u64, _p, _p, _p, _sz, _p]),
     "or_fused_path_bf16": (_int, [_p, _p, _int, _u64, _int, _u64, _u64, _p, _p, _p, _sz, _p]),
+    "or_fused_path_batched": (_int, [_p, _int, _int, _int, _int, _p, _sz, _p]),
 }
+
+
+class or_bucket(C.Structure):
+    _fields_ = [("grads", _p), ("masks", _p), ("out", _p), ("count_out", _p),
+                ("shard_len", _u64), ("seed", _u64), ("base_index", _u64)]
 for _name, (_res, _args) in _SIGS.items():
     _f = getattr(lib, _name)
     _f.restype, _f.argtypes = _res, _args
@@ -174,3 +180,19 @@ def or_fused_path_bf16(grads, masks, N, shard_len, block_log2, seed, base_index,
     w, wb = _ws(workspace)
     _check(lib.or_fused_path_bf16(_ptr(grads), _ptr(masks), N, shard_len, block_log2, seed, base_index, _ptr(out),
                                   _ptr(count_out), w, wb, _stream(stream)), "or_fused_path_bf16")
+
+
+def make_buckets(items):
+    """items: iterable of (grads, masks, out, count_out_or_None, shard_len, seed, base_index) with device
+    tensors -> a host array of or_bucket that or_fused_path_batched can take (reusable across calls)."""
+    items = list(items)
+    arr = (or_bucket * len(items))()
+    for j, (g, m, o, c, L, seed, base) in enumerate(items):
+        arr[j] = or_bucket(_ptr(g), _ptr(m), _ptr(o), _ptr(c), L, seed, base)
+    return arr
+
+
+def or_fused_path_batched(buckets, n_buckets, N, block_log2, bf16, workspace=None, stream=None):
+    w, wb = _ws(workspace)
+    _check(lib.or_fused_path_batched(C.cast(buckets, _p), n_buckets, N, block_log2, int(bool(bf16)), w, wb,
+                                     _stream(stream)), "or_fused_path_batched")

@@ -19,6 +19,13 @@ typedef Geo<K> G;
     return launch_kernel(kernel, dim3((unsigned)units), dim3(G::THREADS), s, pos, a);        \
   }
 
+#define OR_BATCH_LAUNCHER(name, kernel)                                                       \
+  hipError_t name(const BatchArgs& a, unsigned long long units, hipStream_t s, int pos) {   \
+    if (units == 0) return hipSuccess;                                                       \
+    if (units > 0x7FFFFFFFull) return hipErrorInvalidValue;                                  \
+    return launch_kernel(kernel, dim3((unsigned)units), dim3(G::THREADS), s, pos, a);        \
+  }
+
 OR_LAUNCHER(enc_f32, (k_encode<K, float, float>))
 OR_LAUNCHER(enc_bf16, (k_encode<K, bf16_t, bf16_t>))
 OR_LAUNCHER(dec_f32, (k_decode<K, float, false>))
@@ -30,6 +37,8 @@ OR_LAUNCHER(rdec_f32, (k_reduce_decode<K, float, float>))
 OR_LAUNCHER(rdec_bf16, (k_reduce_decode<K, bf16_t, bf16_t>))
 OR_LAUNCHER(fus_f32, (k_fused<K, float, true>))
 OR_LAUNCHER(fus_bf16, (k_fused<K, bf16_t, true>))
+OR_BATCH_LAUNCHER(fusb_f32, (k_fused_batched<K, float>))
+OR_BATCH_LAUNCHER(fusb_bf16, (k_fused_batched<K, bf16_t>))
 #else
 OR_LAUNCHER(fus_f32, (k_fused<K, float, false>))
 OR_LAUNCHER(fus_bf16, (k_fused<K, bf16_t, false>))
@@ -46,7 +55,13 @@ extern const KernelTable OR_CAT(or_kernel_table_, OR_K) = {
 #else
     nullptr, nullptr,
 #endif
-    fus_f32, fus_bf16};
+    fus_f32, fus_bf16,
+#if OR_K <= 14
+    fusb_f32, fusb_bf16
+#else
+    nullptr, nullptr
+#endif
+};
 #endif
 
 }  // namespace orhost

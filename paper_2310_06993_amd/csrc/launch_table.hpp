@@ -28,6 +28,8 @@ inline hipError_t launch_kernel(Kernel kernel, dim3 grid, dim3 block, hipStream_
   return hipGetLastError();
 }
 
+typedef hipError_t (*batch_fn)(const ordev::BatchArgs&, unsigned long long units, hipStream_t, int pos);
+
 struct KernelTable {
   int tile_log2;              // entries per workgroup tile
   launch_fn encode_f32, encode_bf16;
@@ -35,6 +37,7 @@ struct KernelTable {
   launch_fn finalize_decode_f32, finalize_decode_bf16;  // input: fp32 sum + u8 count
   launch_fn reduce_decode_f32, reduce_decode_bf16;      // null when a block spans several tiles
   launch_fn fused_f32, fused_bf16;                      // decode fused in when a block is one tile, else stops at the mean
+  batch_fn fused_batched_f32, fused_batched_bf16;       // null when a block spans several tiles
 };
 
 // class 0 serves every block_log2 <= 10; classes 11..16 serve exactly that block_log2

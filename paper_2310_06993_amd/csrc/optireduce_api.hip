@@ -222,32 +222,39 @@ size_t workspace_bytes(u64 L, int k) {
   return (size_t)(sums + counts);
 }
 
-// shared front of or_reduce_decode* and or_fused_path*
-template <class T>
-or_status path_impl(bool fused, const T* in, const uint32_t* masks, int N, u64 L, int k, u64 seed, u64 base, T* out,
-                    uint8_t* count_out, void* ws, size_t ws_bytes, void* stream, bool bf16) {
-  DisarmOnExit disarm;
+// argument checks shared by or_reduce_decode*, or_fused_path* and the batched form (es = element bytes)
+or_status check_path(const void* in, const uint32_t* masks, int N, u64 L, int k, u64 base, void* out, uint8_t* count_out,
+                     void* ws, size_t ws_bytes, int es) {
   if (!valid_k(k)) return OR_ERR_BLOCK;
-  if (or_status s = check_reduce(in, masks, N, L, sizeof(T))) return s;
+  if (or_status s = check_reduce(in, masks, N, L, es)) return s;
   if (L % ((u64)1 << k)) return OR_ERR_SHAPE;
   if (check_base(k, base)) return OR_ERR_SHAPE;
   if (L == 0) return OR_OK;
   if (!out) return OR_ERR_NULL;
   if (!aligned(out, 16)) return OR_ERR_ALIGN;
-  const u64 in_bytes = (u64)N * L * sizeof(T), mask_bytes = (u64)N * (L / 8);
-  if (ranges_overlap(out, L * sizeof(T), in, in_bytes) || ranges_overlap(out, L * sizeof(T), masks, mask_bytes))
+  const u64 in_bytes = (u64)N * L * es, mask_bytes = (u64)N * (L / 8);
+  if (ranges_overlap(out, L * es, in, in_bytes) || ranges_overlap(out, L * es, masks, mask_bytes))
     return OR_ERR_SHAPE;
   if (count_out && (ranges_overlap(count_out, L, in, in_bytes) || ranges_overlap(count_out, L, masks, mask_bytes) ||
-                    ranges_overlap(count_out, L, out, L * sizeof(T))))
+                    ranges_overlap(count_out, L, out, L * es)))
     return OR_ERR_SHAPE;
   const size_t need = workspace_bytes(L, k);
   if (need) {
     if (!ws || ws_bytes < need) return OR_ERR_WORKSPACE;
     if (!aligned(ws, 256)) return OR_ERR_ALIGN;
     if (ranges_overlap(ws, need, in, in_bytes) || ranges_overlap(ws, need, masks, mask_bytes) ||
-        ranges_overlap(ws, need, out, L * sizeof(T)) || (count_out && ranges_overlap(ws, need, count_out, L)))
+        ranges_overlap(ws, need, out, L * es) || (count_out && ranges_overlap(ws, need, count_out, L)))
       return OR_ERR_SHAPE;
   }
+  return OR_OK;
+}
+
+// enqueue one checked shard: T = float or uint16_t (bf16 bits)
+template <class T>
+or_status run_path(bool fused, const T* in, const uint32_t* masks, int N, u64 L, int k, u64 seed, u64 base, T* out,
+                   uint8_t* count_out, void* ws, void* stream, bool bf16) {
+  if (L == 0) return OR_OK;
+  const size_t need = workspace_bytes(L, k);
   const orhost::KernelTable* t = orhost::table_for_class(class_of(k));
   hipStream_t s = (hipStream_t)stream;
   const u64 units = (L + ((u64)1 << t->tile_log2) - 1) >> t->tile_log2;
@@ -276,6 +283,61 @@ or_status path_impl(bool fused, const T* in, const uint32_t* masks, int N, u64 L
     return finish(e);
   d.count_in = cnt;
   return finish((bf16 ? t->finalize_decode_bf16 : t->finalize_decode_f32)(d, units, s, orhost::LAUNCH_LAST));
+}
+
+template <class T>
+or_status path_impl(bool fused, const T* in, const uint32_t* masks, int N, u64 L, int k, u64 seed, u64 base, T* out,
+                    uint8_t* count_out, void* ws, size_t ws_bytes, void* stream, bool bf16) {
+  DisarmOnExit disarm;
+  if (or_status s = check_path(in, masks, N, L, k, base, out, count_out, ws, ws_bytes, sizeof(T))) return s;
+  return run_path<T>(fused, in, masks, N, L, k, seed, base, out, count_out, ws, stream, bf16);
+}
+
+or_status batched_impl(const or_bucket* buckets, int n, int N, int k, bool bf16, void* ws, size_t ws_bytes, void* stream) {
+  DisarmOnExit disarm;
+  if (n < 0) return OR_ERR_SHAPE;
+  if (n == 0) return OR_OK;
+  if (!buckets) return OR_ERR_NULL;
+  const int es = bf16 ? 2 : 4;
+  for (int j = 0; j < n; ++j) {   // every bucket is checked before anything is enqueued
+    const or_bucket& q = buckets[j];
+    if (or_status s = check_path(q.grads, q.masks, N, q.shard_len, k, q.base_index, q.out, q.count_out, ws, ws_bytes, es))
+      return s;
+  }
+  const orhost::KernelTable* t = orhost::table_for_class(class_of(k));
+  orhost::batch_fn f = bf16 ? t->fused_batched_bf16 : t->fused_batched_f32;
+  if (!f) {   // blocks above 2^14: one bucket after the other, sharing the workspace in stream order
+    for (int j = 0; j < n; ++j) {
+      const or_bucket& q = buckets[j];
+      or_status s = bf16 ? run_path<uint16_t>(true, (const uint16_t*)q.grads, q.masks, N, q.shard_len, k, q.seed,
+                                              q.base_index, (uint16_t*)q.out, q.count_out, ws, stream, true)
+                         : run_path<float>(true, (const float*)q.grads, q.masks, N, q.shard_len, k, q.seed, q.base_index,
+                                           (float*)q.out, q.count_out, ws, stream, false);
+      if (s) return s;
+    }
+    return OR_OK;
+  }
+  for (int j0 = 0; j0 < n; j0 += ordev::kMaxBatch) {
+    ordev::BatchArgs ba = {};
+    ba.N = N; ba.k = k; ba.scale = scale_of(k);
+    u64 tiles = 0;
+    int m = 0;
+    for (int j = j0; j < n && m < ordev::kMaxBatch; ++j) {
+      const or_bucket& q = buckets[j];
+      if (q.shard_len == 0) continue;
+      const u64 units = (q.shard_len + ((u64)1 << t->tile_log2) - 1) >> t->tile_log2;
+      if (tiles + units > 0x7FFFFFFFull) return OR_ERR_SHAPE;
+      ba.tile_start[m] = (uint32_t)tiles;
+      ba.b[m] = {q.grads, q.masks, q.out, q.count_out, q.shard_len, q.seed, q.base_index};
+      tiles += units;
+      ++m;
+    }
+    ba.n = m;
+    ba.tile_start[m] = (uint32_t)tiles;
+    if (m == 0) continue;
+    if (hipError_t e = f(ba, tiles, (hipStream_t)stream, orhost::LAUNCH_ONLY)) return finish(e);
+  }
+  return OR_OK;
 }
 
 }  // namespace
@@ -371,6 +433,11 @@ or_status or_fused_path_bf16(const uint16_t* grads, const uint32_t* masks, int N
                              void* workspace, size_t workspace_bytes, void* stream) {
   return path_impl<uint16_t>(true, grads, masks, N, shard_len, block_log2, seed, base_index, out, count_out, workspace,
                              workspace_bytes, stream, true);
+}
+
+or_status or_fused_path_batched(const or_bucket* buckets, int n_buckets, int N, int block_log2, int bf16,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+  return batched_impl(buckets, n_buckets, N, block_log2, bf16 != 0, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

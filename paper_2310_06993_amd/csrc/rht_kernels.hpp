@@ -248,14 +248,13 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_reduce_decode(PathArgs a) {
 // No register prefetch of the next worker's tile: measured on MI355X, keeping the kernel small enough
 // for several independent workgroups per CU hides the load latency better than a second tile buffer.
 template <int K, class In, bool DECODE>
-__global__ __launch_bounds__(Geo<K>::THREADS) __attribute__((amdgpu_waves_per_eu(Geo<K>::R == 32 ? 4 : 1)))
-void k_fused(PathArgs a) {
+__device__ __forceinline__ void fused_tile(const PathArgs& a, u64 unit) {
   constexpr int T = Geo<K>::T, NB = kXbufs<K>, R = Geo<K>::R;
   constexpr bool FULL = kShardTilesFull<K>;
   static_assert(DECODE == (Geo<K>::PARTS == 1), "decode in the same kernel only when a block is one tile");
   __shared__ float xbuf[NB ? NB : 1][NB ? T : 1];
   const int wave = wave_id(), lane = lane_id(), kt = tile_bits<K>(a.k);
-  const u64 unit = blockIdx.x, L = a.n_pad, e0 = unit * T;
+  const u64 L = a.n_pad, e0 = unit * T;
   const In* grads = (const In*)a.in;
   const float sigma = lane_sigma(lane, kt < 6 ? kt : 6);
   // a power-of-two scale commutes with rounding to the wire type; any other scale is applied first
@@ -306,6 +305,43 @@ void k_fused(PathArgs a) {
   } else {
     store_tile<K, true, FULL>(a.mean_out, e0, L, wave, lane, acc);
   }
+}
+
+template <int K, class In, bool DECODE>
+__global__ __launch_bounds__(Geo<K>::THREADS) __attribute__((amdgpu_waves_per_eu(Geo<K>::R == 32 ? 4 : 1)))
+void k_fused(PathArgs a) {
+  fused_tile<K, In, DECODE>(a, blockIdx.x);
+}
+
+// Several buckets of one launch shape class (same N, block size and type) in ONE launch: small buckets
+// (a 25 MiB DDP bucket is only ~100 tiles per shard) cannot fill 256 CUs on their own.  Descriptors ride
+// in the kernel arguments; workgroup x serves tile x - tile_start[j] of bucket j.
+constexpr int kMaxBatch = 32;
+struct BucketArgs {
+  const void* in;
+  const uint32_t* masks;
+  void* out;
+  uint8_t* count_out;
+  u64 shard_len, seed, base;
+};
+struct BatchArgs {
+  int n, N, k;
+  float scale;
+  uint32_t tile_start[kMaxBatch + 1];
+  BucketArgs b[kMaxBatch];
+};
+
+template <int K, class In>
+__global__ __launch_bounds__(Geo<K>::THREADS) __attribute__((amdgpu_waves_per_eu(Geo<K>::R == 32 ? 4 : 1)))
+void k_fused_batched(BatchArgs ba) {
+  const uint32_t x = blockIdx.x;
+  int j = 0;
+  while (j + 1 < ba.n && ba.tile_start[j + 1] <= x) ++j;
+  PathArgs a = {};
+  a.in = ba.b[j].in; a.masks = ba.b[j].masks; a.out = ba.b[j].out; a.count_out = ba.b[j].count_out;
+  a.n = a.n_pad = ba.b[j].shard_len; a.seed = ba.b[j].seed; a.base = ba.b[j].base;
+  a.N = ba.N; a.k = ba.k; a.scale = ba.scale;
+  fused_tile<K, In, true>(a, x - ba.tile_start[j]);
 }
 
 }  // namespace ordev

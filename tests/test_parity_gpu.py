@@ -330,3 +330,51 @@ def test_errors_leave_outputs_untouched(b):
     assert e.value.status == 6
     torch.cuda.synchronize()
     assert bool((out == 7.0).all())
+
+
+@pytest.mark.parametrize("k,kind", [(12, "f32"), (10, "bf16"), (16, "f32")])
+def test_batched_buckets_equal_single_calls(b, orc, k, kind):
+    # buckets of different lengths in one call (more than 32 of them for k = 12: several launches)
+    B = 1 << k
+    N = 4
+    lens = [B * (1 + j % 3) for j in range(35)] if k == 12 else [2 * B, B, 0, 3 * B]
+    dt = torch.float32 if kind == "f32" else torch.bfloat16
+    gen = torch.Generator(device=dev()).manual_seed(k)
+    items, singles = [], []
+    nws = max(b.or_workspace_bytes(L, k) for L in lens)
+    ws = torch.empty(nws, dtype=torch.uint8, device=dev()) if nws else None
+    for j, L in enumerate(lens):
+        g = (torch.randn((N, L), device=dev(), generator=gen) * 1e-3).to(dt)
+        m = torch.randint(-2 ** 31, 2 ** 31 - 1, (N, L // 32), device=dev(), generator=gen, dtype=torch.int64).to(torch.int32)
+        m |= torch.randint(-2 ** 31, 2 ** 31 - 1, (N, L // 32), device=dev(), generator=gen, dtype=torch.int64).to(torch.int32)
+        if L:
+            m[j % N] = -1
+        out = torch.full((L,), float("nan"), device=dev()).to(dt)
+        cnt = torch.zeros(L, dtype=torch.uint8, device=dev()) if j % 2 == 0 else None
+        items.append((g, m, out, cnt, L, 100 + j, j * 4 * max(B, 128)))
+        out1 = torch.empty(L, dtype=dt, device=dev())
+        cnt1 = torch.empty(L, dtype=torch.uint8, device=dev())
+        (b.or_fused_path if kind == "f32" else b.or_fused_path_bf16)(g, m, N, L, k, 100 + j, j * 4 * max(B, 128), out1, cnt1, ws)
+        singles.append((out1, cnt1))
+    arr = b.make_buckets(items)
+    b.or_fused_path_batched(arr, len(items), N, k, kind == "bf16", ws)
+    torch.cuda.synchronize()
+    for (g, m, out, cnt, L, seed, base), (out1, cnt1) in zip(items, singles):
+        assert torch.equal(out.view(torch.int16 if kind == "bf16" else torch.int32),
+                           out1.view(torch.int16 if kind == "bf16" else torch.int32))
+        if cnt is not None:
+            assert torch.equal(cnt, cnt1)
+    # and one of them against the oracle
+    g, m, out, cnt, L, seed, base = items[1]
+    want, _ = orc.fused_path(to_np(g), to_np(m), k, seed, base)
+    assert rel_l2(to_np(out), want) <= TOL[kind]
+    # a bad bucket anywhere in the list stops the whole call before anything runs
+    bad = list(items)
+    g, m, out, cnt, L, seed, base = bad[-1]
+    bad[-1] = (g, m, out, cnt, L, seed, base + 32)
+    items[0][2].fill_(5.0)
+    with pytest.raises(b.OptiReduceError) as e:
+        b.or_fused_path_batched(b.make_buckets(bad), len(bad), N, k, kind == "bf16", ws)
+    assert e.value.status == 4
+    torch.cuda.synchronize()
+    assert bool((items[0][2].float() == 5.0).all())
