@@ -13,10 +13,15 @@ constexpr int K = OR_K;
 typedef Geo<K> G;
 
 #define OR_LAUNCHER(name, kernel)                                                            \
+  /* serves output tiles a.unit0 .. a.unit0 + units - 1 */                                  \
   hipError_t name(const PathArgs& a, unsigned long long units, hipStream_t s, int pos) {    \
     if (units == 0) return hipSuccess;                                                       \
-    if (units > 0x7FFFFFFFull) return hipErrorInvalidValue;                                  \
-    return launch_kernel(kernel, dim3((unsigned)units), dim3(G::THREADS), s, pos, a);        \
+    PathArgs b = a;                                                                          \
+    b.unit_end = a.unit0 + units;                                                            \
+    unsigned long long grid = units;                                                         \
+    if (G::PARTS > 1) grid = (units + 8 * G::PARTS - 1) / (8 * G::PARTS) * (8 * G::PARTS);   \
+    if (grid > 0x7FFFFFFFull) return hipErrorInvalidValue;                                   \
+    return launch_kernel(kernel, dim3((unsigned)grid), dim3(G::THREADS), s, pos, b);         \
   }
 
 #define OR_BATCH_LAUNCHER(name, kernel)                                                       \
@@ -26,12 +31,30 @@ typedef Geo<K> G;
     return launch_kernel(kernel, dim3((unsigned)units), dim3(G::THREADS), s, pos, a);        \
   }
 
-OR_LAUNCHER(enc_f32, (k_encode<K, float, float>))
-OR_LAUNCHER(enc_bf16, (k_encode<K, bf16_t, bf16_t>))
-OR_LAUNCHER(dec_f32, (k_decode<K, float, false>))
-OR_LAUNCHER(dec_bf16, (k_decode<K, bf16_t, false>))
-OR_LAUNCHER(fdec_f32, (k_decode<K, float, true>))
-OR_LAUNCHER(fdec_bf16, (k_decode<K, bf16_t, true>))
+#define OR_SPLIT_LAUNCHER(name, kernel_full, kernel_tail)                                    \
+  OR_LAUNCHER(name##_full, kernel_full)                                                      \
+  OR_LAUNCHER(name##_tail, kernel_tail)                                                      \
+  /* a.unit0 = number of leading tiles that need no bounds checks; the rest go to the checked kernel */ \
+  hipError_t name(const PathArgs& a, unsigned long long units, hipStream_t s, int pos) {    \
+    const unsigned long long nfull = a.unit0 < units ? a.unit0 : units, ntail = units - nfull; \
+    PathArgs b = a;                                                                          \
+    b.unit0 = 0;                                                                             \
+    if (nfull) {                                                                             \
+      if (hipError_t e = name##_full(b, nfull, s, ntail ? (pos & LAUNCH_FIRST) : pos)) return e; \
+    }                                                                                        \
+    if (ntail) {                                                                             \
+      b.unit0 = nfull;                                                                       \
+      return name##_tail(b, ntail, s, nfull ? (pos & LAUNCH_LAST) : pos);                    \
+    }                                                                                        \
+    return hipSuccess;                                                                       \
+  }
+
+OR_SPLIT_LAUNCHER(enc_f32, (k_encode<K, float, float, true>), (k_encode<K, float, float, false>))
+OR_SPLIT_LAUNCHER(enc_bf16, (k_encode<K, bf16_t, bf16_t, true>), (k_encode<K, bf16_t, bf16_t, false>))
+OR_SPLIT_LAUNCHER(dec_f32, (k_decode<K, float, false, true>), (k_decode<K, float, false, false>))
+OR_SPLIT_LAUNCHER(dec_bf16, (k_decode<K, bf16_t, false, true>), (k_decode<K, bf16_t, false, false>))
+OR_SPLIT_LAUNCHER(fdec_f32, (k_decode<K, float, true, true>), (k_decode<K, float, true, false>))
+OR_SPLIT_LAUNCHER(fdec_bf16, (k_decode<K, bf16_t, true, true>), (k_decode<K, bf16_t, true, false>))
 #if OR_K <= 14
 OR_LAUNCHER(rdec_f32, (k_reduce_decode<K, float, float>))
 OR_LAUNCHER(rdec_bf16, (k_reduce_decode<K, bf16_t, bf16_t>))

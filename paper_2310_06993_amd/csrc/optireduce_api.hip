@@ -129,6 +129,13 @@ u64 padded(u64 n, int k) {
   return (n + B - 1) / B * B;
 }
 
+// number of leading tiles that lie, together with every other tile of their transform block, wholly inside
+// the first n entries (those need no bounds checks)
+u64 full_units(u64 n, int k, int tile_log2) {
+  const int group_log2 = k > tile_log2 ? k : tile_log2;   // a block above 2^14 spans 2^(k-14) tiles
+  return (n >> group_log2) << (group_log2 - tile_log2);
+}
+
 float scale_of(int k) { return (float)(1.0 / sqrt((double)((u64)1 << k))); }
 
 or_status check_base(int k, u64 base) {
@@ -162,6 +169,7 @@ or_status encode_impl(const T* grad, u64 n, int k, u64 seed, u64 base, T* out, v
   PathArgs a = {};
   a.in = grad; a.out = out; a.n = n; a.n_pad = n_pad; a.seed = seed; a.base = base; a.k = k; a.scale = scale_of(k);
   const u64 units = (n_pad + ((u64)1 << t->tile_log2) - 1) >> t->tile_log2;
+  a.unit0 = full_units(n, k, t->tile_log2);   // tiles whose whole block lies inside the n valid entries
   return finish((bf16 ? t->encode_bf16 : t->encode_f32)(a, units, (hipStream_t)stream, orhost::LAUNCH_ONLY));
 }
 
@@ -181,6 +189,7 @@ or_status decode_impl(const float* agg, const uint8_t* count, bool finalize, u64
   a.in = agg; a.count_in = count; a.out = out; a.n = n; a.n_pad = n_pad; a.seed = seed; a.base = base; a.k = k;
   a.scale = scale_of(k);
   const u64 units = (n_pad + ((u64)1 << t->tile_log2) - 1) >> t->tile_log2;
+  a.unit0 = full_units(n, k, t->tile_log2);
   orhost::launch_fn f = finalize ? (bf16 ? t->finalize_decode_bf16 : t->finalize_decode_f32)
                                  : (bf16 ? t->decode_bf16 : t->decode_f32);
   return finish(f(a, units, (hipStream_t)stream, orhost::LAUNCH_ONLY));
@@ -271,6 +280,7 @@ or_status run_path(bool fused, const T* in, const uint32_t* masks, int N, u64 L,
   PathArgs d = {};
   d.out = out; d.n = L; d.n_pad = L; d.seed = seed; d.base = base; d.k = k; d.scale = a.scale;
   d.in = ws_f32;
+  d.unit0 = units;   // shards hold whole blocks: no tile of the decode needs bounds checks
   if (fused) {
     a.mean_out = ws_f32;
     a.out = nullptr;

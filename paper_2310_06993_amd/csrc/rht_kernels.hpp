@@ -16,6 +16,8 @@ struct PathArgs {
   u64 n_pad;               // padded length = vector length on the encoded side; shard_len for reduce/fused
   u64 seed;
   u64 base;                // index of entry 0 in the sign stream
+  u64 unit0;               // first output tile served by this launch
+  u64 unit_end;            // one past the last output tile served by this launch (set by the launcher)
   int N;                   // workers
   int k;                   // block_log2
   float scale;             // 2^(-k/2) rounded to fp32
@@ -26,48 +28,97 @@ template <int K> constexpr bool kShardTilesFull = (K != 0);
 // LDS buffers for the exchange: two (one barrier per exchange) while they fit several workgroups per CU.
 template <int K> constexpr int kXbufs = (Geo<K>::Q == 0) ? 0 : (Geo<K>::T * 4 <= 16384 ? 2 : 1);
 
+// Which output tile a workgroup serves.  When a block spans PARTS tiles, the PARTS workgroups of one block
+// all read the same input tiles; consecutive workgroup ids go round-robin over the 8 XCDs (each with its
+// own L2), so the ids are remapped to put a block's workgroups on ONE XCD, next to each other in dispatch
+// order.  The launcher rounds the grid up to a multiple of 8*PARTS; ids that map at or past `unit_end`
+// (the end of THIS launch's range, not of the vector) return `none`.
+template <int K>
+__device__ __forceinline__ u64 unit_of_workgroup(u64 unit0, u64 unit_end, bool& none) {
+  constexpr int HB = Geo<K>::HB, PARTS = Geo<K>::PARTS;
+  none = false;
+  if constexpr (PARTS == 1) {
+    return unit0 + blockIdx.x;
+  } else {
+    const u64 x = blockIdx.x, slot = x >> 3;
+    const u64 blk = ((slot >> HB) << 3) + (x & 7);
+    const u64 unit = unit0 + (blk << HB) + (slot & (PARTS - 1));
+    none = unit >= unit_end;
+    return unit;
+  }
+}
+
 // +1/-1 entry of H_{2^HB}: row `part`, column q
 __device__ __forceinline__ float part_coef(int part, int q) { return (__builtin_popcount(part & q) & 1) ? -1.0f : 1.0f; }
 
 template <int K>
 __device__ __forceinline__ int tile_bits(int k) { return K ? Geo<K>::KT : k; }
 
-// Raw tile(s) of one worker in layout A, before signs.  For blocks above 2^14 the +-1 combination of
-// the block's tiles that feeds output tile `unit` is formed here, signs applied per input tile.
+// Sign words (see sign_words) of the PARTS input tiles that feed output tile `unit`; blocks above 2^14 only.
+template <int K>
+__device__ __forceinline__ void part_sign_words(u64 unit, u64 seed, u64 base, int wave, uint32_t (&sw)[Geo<K>::PARTS]) {
+  constexpr int T = Geo<K>::T, HB = Geo<K>::HB, PARTS = Geo<K>::PARTS;
+  const u64 blk = unit >> HB;
+#pragma unroll
+  for (int q = 0; q < PARTS; ++q)
+    sw[q] = sign_words<Geo<K>::R>(seed, base + ((blk << HB) + q) * T + (u64)wave * Geo<K>::WAVE_ENTRIES);
+}
+
+// v = sum over the block's PARTS input tiles q of H_{PARTS}[part][q] * (signed tile q), layout A
+template <int K, bool ALL_FULL, class In>
+__device__ __forceinline__ void combine_parts(const In* __restrict__ x, u64 limit, u64 blk, int part, int wave, int lane,
+                                              float (&v)[Geo<K>::R], const uint32_t (&sw)[Geo<K>::PARTS]) {
+  constexpr int T = Geo<K>::T, HB = Geo<K>::HB, PARTS = Geo<K>::PARTS, R = Geo<K>::R;
+#pragma unroll
+  for (int q = 0; q < PARTS; ++q) {
+    float t[R];
+    load_tile<K, false, ALL_FULL>(x, ((blk << HB) + q) * T, limit, wave, lane, t);
+    const float c = part_coef(part, q);
+    uint32_t w = sw[q];
+    asm volatile("" : "+v"(w));   // keeps the lane masks of tile q from being formed before tile q is reached
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const float ts = in_mask(mask_of_reg(w, r)) ? -t[r] : t[r];
+      v[r] = q == 0 ? c * ts : __builtin_fmaf(c, ts, v[r]);
+    }
+    __builtin_amdgcn_sched_barrier(0);   // one input tile at a time: bounds the live lane masks and tile registers
+  }
+}
+
+// Raw tile of one worker in layout A.  One tile per block: the plain tile, signs still to be applied by
+// the caller.  Blocks above 2^14: the signed +-1 combination of the block's PARTS tiles that feeds output
+// tile `unit` (H_{2^k} = H_{2^(k-14)} (x) H_{2^14}), with the signs taken from `sw`.
 template <int K, bool FULL, class In>
-__device__ __forceinline__ void load_raw_tile(const In* __restrict__ x, u64 limit, u64 unit, u64 seed, u64 base,
-                                              int wave, int lane, float (&v)[Geo<K>::R]) {
+__device__ __forceinline__ void load_raw_tile(const In* __restrict__ x, u64 limit, u64 unit, int wave, int lane,
+                                              float (&v)[Geo<K>::R], const uint32_t (&sw)[Geo<K>::PARTS]) {
   constexpr int T = Geo<K>::T, HB = Geo<K>::HB, PARTS = Geo<K>::PARTS, R = Geo<K>::R;
   if constexpr (PARTS == 1) {
     load_tile<K, false, FULL>(x, unit * T, limit, wave, lane, v);
   } else {
     const u64 blk = unit >> HB;
     const int part = (int)(unit & (PARTS - 1));
-#pragma unroll
-    for (int r = 0; r < R; ++r) v[r] = 0.0f;
-    for (int q = 0; q < PARTS; ++q) {
-      const u64 tq = (blk << HB) + q;
-      float t[R];
-      u64 sg[R];
-      load_tile<K, false, FULL>(x, tq * T, limit, wave, lane, t);
-      sign_masks(seed, base + tq * T + (u64)wave * Geo<K>::WAVE_ENTRIES, sg);
-      apply_signs(t, sg);
-      const float c = part_coef(part, q);
-#pragma unroll
-      for (int r = 0; r < R; ++r) v[r] = __builtin_fmaf(c, t[r], v[r]);
-    }
+    // one decision for the whole block keeps each branch straight-line code
+    if (FULL || ((blk + 1) << HB) * T <= limit) combine_parts<K, true>(x, limit, blk, part, wave, lane, v, sw);
+    else combine_parts<K, false>(x, limit, blk, part, wave, lane, v, sw);
   }
 }
 
 // Sec. 3.3 encode: out = B^(-1/2) H D x, blockwise; pad of the last block is zero.
-template <int K, class In, class Wire>
+// FULL = true: every tile of this launch lies wholly inside the input and the output (no bounds checks);
+// the host sends the ragged end of a vector to a FULL = false launch of its own, so that the checked
+// accesses do not cost the common case registers.
+template <int K, class In, class Wire, bool FULL>
 __global__ __launch_bounds__(Geo<K>::THREADS) void k_encode(PathArgs a) {
   constexpr int T = Geo<K>::T, R = Geo<K>::R;
   __shared__ float xbuf[Geo<K>::Q > 0 ? T : 1];
   const int wave = wave_id(), lane = lane_id(), kt = tile_bits<K>(a.k);
-  const u64 unit = blockIdx.x;
+  bool none;
+  const u64 unit = unit_of_workgroup<K>(a.unit0, a.unit_end, none);
+  if (none) return;
   float v[R];
-  load_raw_tile<K, false>((const In*)a.in, a.n, unit, a.seed, a.base, wave, lane, v);
+  uint32_t sw[Geo<K>::PARTS] = {};
+  if constexpr (Geo<K>::PARTS > 1) part_sign_words<K>(unit, a.seed, a.base, wave, sw);
+  load_raw_tile<K, FULL>((const In*)a.in, a.n, unit, wave, lane, v, sw);
   if constexpr (Geo<K>::PARTS == 1) {
     u64 sg[R];
     sign_masks(a.seed, a.base + unit * T + (u64)wave * Geo<K>::WAVE_ENTRIES, sg);
@@ -77,34 +128,36 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_encode(PathArgs a) {
   const float c = a.scale * lane_sigma(lane, kt < 6 ? kt : 6);
 #pragma unroll
   for (int r = 0; r < R; ++r) v[r] *= c;
-  store_tile<K, true, false>((Wire*)a.out, unit * T, a.n_pad, wave, lane, v);
+  store_tile<K, true, FULL>((Wire*)a.out, unit * T, a.n_pad, wave, lane, v);
 }
 
 // Mean tile (layout B) for decode: either the mean itself, or sum / count with 0 where count is 0
 // (the "averages" of Sec. 3.1.1 taken over the entries that arrived).
-template <int K, bool FINALIZE>
+template <int K, bool FINALIZE, bool FULL>
 __device__ __forceinline__ void load_mean_tile(const PathArgs& a, u64 tile, int wave, int lane,
                                                float (&v)[Geo<K>::R]) {
   constexpr int T = Geo<K>::T, R = Geo<K>::R;
-  load_tile<K, true, false>((const float*)a.in, tile * T, a.n_pad, wave, lane, v);
+  load_tile<K, true, FULL>((const float*)a.in, tile * T, a.n_pad, wave, lane, v);
   if constexpr (FINALIZE) {
     float c[R];
-    load_tile<K, true, false>(a.count_in, tile * T, a.n_pad, wave, lane, c);
+    load_tile<K, true, FULL>(a.count_in, tile * T, a.n_pad, wave, lane, c);
 #pragma unroll
     for (int r = 0; r < R; ++r) v[r] = c[r] > 0.0f ? v[r] / c[r] : 0.0f;
   }
 }
 
 // Sec. 3.3 / Sec. 4 decode: out = D B^(-1/2) H mean, first n entries kept.
-template <int K, class Out, bool FINALIZE>
+template <int K, class Out, bool FINALIZE, bool FULL>
 __global__ __launch_bounds__(Geo<K>::THREADS) void k_decode(PathArgs a) {
   constexpr int T = Geo<K>::T, HB = Geo<K>::HB, PARTS = Geo<K>::PARTS, R = Geo<K>::R;
   __shared__ float xbuf[Geo<K>::Q > 0 ? T : 1];
   const int wave = wave_id(), lane = lane_id(), kt = tile_bits<K>(a.k);
-  const u64 unit = blockIdx.x;
+  bool none;
+  const u64 unit = unit_of_workgroup<K>(a.unit0, a.unit_end, none);
+  if (none) return;
   float v[R];
   if constexpr (PARTS == 1) {
-    load_mean_tile<K, FINALIZE>(a, unit, wave, lane, v);
+    load_mean_tile<K, FINALIZE, FULL>(a, unit, wave, lane, v);
   } else {
     const u64 blk = unit >> HB;
     const int part = (int)(unit & (PARTS - 1));
@@ -112,7 +165,7 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_decode(PathArgs a) {
     for (int r = 0; r < R; ++r) v[r] = 0.0f;
     for (int q = 0; q < PARTS; ++q) {
       float t[R];
-      load_mean_tile<K, FINALIZE>(a, (blk << HB) + q, wave, lane, t);
+      load_mean_tile<K, FINALIZE, FULL>(a, (blk << HB) + q, wave, lane, t);
       const float c = part_coef(part, q);
 #pragma unroll
       for (int r = 0; r < R; ++r) v[r] = __builtin_fmaf(c, t[r], v[r]);
@@ -125,7 +178,7 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_decode(PathArgs a) {
 #pragma unroll
   for (int r = 0; r < R; ++r) v[r] *= c;
   apply_signs(v, sg);
-  store_tile<K, false, false>((Out*)a.out, unit * T, a.n, wave, lane, v);
+  store_tile<K, false, FULL>((Out*)a.out, unit * T, a.n, wave, lane, v);
 }
 
 // acc += value where the worker's copy arrived.  Arrivals are counted as `full` (workers whose whole
@@ -158,16 +211,10 @@ __device__ __forceinline__ void store_counts(uint8_t* count_out, u64 e0, u64 lim
                                              const uint32_t (&cntp)[Geo<K>::R / 4], int full) {
   constexpr int R = Geo<K>::R;
   if (!count_out) return;
+  float c[R];
 #pragma unroll
-  for (int r = 0; r < R; ++r) {
-    const uint8_t c = (uint8_t)count_of<R>(cntp, full, r);
-    if (FULL) {
-      store_one<true>(&(count_out + e0 + off_b<K>(wave, r))[(unsigned)lane], c);
-    } else {
-      const u64 e = e0 + off_b<K>(wave, r) + lane;
-      if (e < limit) store_one<true>(count_out + e, c);
-    }
-  }
+  for (int r = 0; r < R; ++r) c[r] = (float)count_of<R>(cntp, full, r);
+  store_tile<K, true, FULL, true>(count_out, e0, limit, wave, lane, c);
   __builtin_amdgcn_sched_barrier(0);
 }
 
@@ -260,7 +307,9 @@ __device__ __forceinline__ void fused_tile(const PathArgs& a, u64 unit) {
   // a power-of-two scale commutes with rounding to the wire type; any other scale is applied first
   const bool scale_first = sizeof(In) == 2 && (a.k & 1);
   u64 sg[R];
+  uint32_t sw[Geo<K>::PARTS] = {};
   if constexpr (Geo<K>::PARTS == 1) sign_masks(a.seed, a.base + e0 + (u64)wave * Geo<K>::WAVE_ENTRIES, sg);
+  else part_sign_words<K>(unit, a.seed, a.base, wave, sw);
   float acc[R], va[R];
   uint32_t cnt[R / 4];
   int full = 0, flip = 0;
@@ -286,7 +335,7 @@ __device__ __forceinline__ void fused_tile(const PathArgs& a, u64 unit) {
   };
 
   for (int i = 0; i < a.N; ++i) {
-    load_raw_tile<K, FULL>(grads + (u64)i * L, L, unit, a.seed, a.base, wave, lane, va);
+    load_raw_tile<K, FULL>(grads + (u64)i * L, L, unit, wave, lane, va, sw);
     ma = load_mask_words<K, FULL>(a.masks + (u64)i * mrow, e0, L, moff);
     step(va, ma);
   }
@@ -310,7 +359,10 @@ __device__ __forceinline__ void fused_tile(const PathArgs& a, u64 unit) {
 template <int K, class In, bool DECODE>
 __global__ __launch_bounds__(Geo<K>::THREADS) __attribute__((amdgpu_waves_per_eu(Geo<K>::R == 32 ? 4 : 1)))
 void k_fused(PathArgs a) {
-  fused_tile<K, In, DECODE>(a, blockIdx.x);
+  bool none;
+  const u64 unit = unit_of_workgroup<K>(a.unit0, a.unit_end, none);
+  if (none) return;
+  fused_tile<K, In, DECODE>(a, unit);
 }
 
 // Several buckets of one launch shape class (same N, block size and type) in ONE launch: small buckets

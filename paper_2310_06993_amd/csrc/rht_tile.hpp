@@ -129,6 +129,19 @@ __device__ __forceinline__ void sign_masks(u64 seed, u64 g, u64 (&sg)[NR]) {
   }
 }
 
+// The same sign bits as one vector register: lane l holds 32-bit word l of the 2*NR words that cover the
+// wavefront's NR registers (word 2r, 2r+1 = the lane mask of register r), in the format of
+// load_mask_words, so mask_of_reg() turns it into lane masks.  Used where several input tiles each need
+// their own signs and scalar registers cannot hold them all.
+template <int NR>
+__device__ __forceinline__ uint32_t sign_words(u64 seed, u64 g) {
+  const int l = lane_id() & (2 * NR - 1);
+  u64 ctr = (g >> 7) + (u64)(l >> 2);
+  u32x4 w = philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), 0u, 0u, (uint32_t)seed, (uint32_t)(seed >> 32));
+  const int c = l & 3;
+  return c == 0 ? w.a : (c == 1 ? w.b : (c == 2 ? w.c : w.d));
+}
+
 __device__ __forceinline__ bool in_mask(u64 m) { return __builtin_amdgcn_inverse_ballot_w64(m); }
 
 template <int NR>
@@ -287,22 +300,49 @@ __device__ __forceinline__ void transform(float (&v)[Geo<K>::R], float* xbuf, in
 // `p` points at entry 0 of the vector, `e0` is the tile's first entry, `limit` the number of valid
 // entries of the vector; entries at or beyond `limit` read as zero / are not written.  FULL = true
 // promises e0 + tile <= limit.
+// A tile that may be cut short by `limit` goes through raw buffer accesses: the descriptor covers exactly
+// the valid bytes of the tile, so the hardware range check returns 0 for loads beyond it and drops stores
+// beyond it -- no per-lane compares or exec masks.
+template <class T>
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const T* p, u64 e0, u64 limit) {
+  const u64 left = limit > e0 ? (limit - e0) * sizeof(T) : 0;
+  const int bytes = left > 0x7FFFFFFFull ? 0x7FFFFFFF : (int)left;
+  return __builtin_amdgcn_make_buffer_rsrc((void*)(p + e0), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ float buf_load(__amdgpu_buffer_rsrc_t r, int entry, const float*) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, entry * 4, 0, 0));
+}
+__device__ __forceinline__ float buf_load(__amdgpu_buffer_rsrc_t r, int entry, const bf16_t*) {
+  return __builtin_bit_cast(float, (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(r, entry * 2, 0, 0) << 16);
+}
+__device__ __forceinline__ float buf_load(__amdgpu_buffer_rsrc_t r, int entry, const uint8_t*) {
+  return (float)__builtin_amdgcn_raw_buffer_load_b8(r, entry, 0, 0);
+}
+__device__ __forceinline__ void buf_store(__amdgpu_buffer_rsrc_t r, int entry, float v, float*) {
+  __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, entry * 4, 0, 0);
+}
+__device__ __forceinline__ void buf_store(__amdgpu_buffer_rsrc_t r, int entry, float v, bf16_t*) {
+  __builtin_amdgcn_raw_buffer_store_b16(from_f32<bf16_t>(v).bits, r, entry * 2, 0, 0);
+}
+__device__ __forceinline__ void buf_store(__amdgpu_buffer_rsrc_t r, int entry, float v, uint8_t*) {
+  __builtin_amdgcn_raw_buffer_store_b8(from_f32<uint8_t>(v), r, entry, 0, 0);
+}
+
 template <int K, bool LAYOUT_B, bool FULL, class T>
 __device__ __forceinline__ void load_tile(const T* __restrict__ p, u64 e0, u64 limit, int wave, int lane,
                                           float (&v)[Geo<K>::R]) {
   constexpr int R = Geo<K>::R;
   if (FULL || e0 + Geo<K>::T <= limit) {
-    // uniform base (scalar registers) + 32-bit lane offset: one address register for the whole tile
+    // uniform base (scalar registers) + 32-bit lane offset
     const T* q = p + e0;
     const unsigned l = (unsigned)lane;
 #pragma unroll
     for (int r = 0; r < R; ++r) v[r] = to_f32((q + (LAYOUT_B ? off_b<K>(wave, r) : off_a<K>(wave, r)))[l]);
   } else {
+    const __amdgpu_buffer_rsrc_t rs = tile_rsrc(p, e0, limit);
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      u64 e = e0 + (LAYOUT_B ? off_b<K>(wave, r) : off_a<K>(wave, r)) + lane;
-      v[r] = e < limit ? to_f32(p[e]) : 0.0f;
-    }
+    for (int r = 0; r < R; ++r)
+      v[r] = buf_load(rs, (LAYOUT_B ? off_b<K>(wave, r) : off_a<K>(wave, r)) + lane, (const T*)nullptr);
   }
 }
 
@@ -319,11 +359,10 @@ __device__ __forceinline__ void store_tile(T* __restrict__ p, u64 e0, u64 limit,
     for (int r = 0; r < R; ++r)
       store_one<NT>(&(q + (LAYOUT_B ? off_b<K>(wave, r) : off_a<K>(wave, r)))[l], from_f32<T>(v[r]));
   } else {
+    const __amdgpu_buffer_rsrc_t rs = tile_rsrc(p, e0, limit);
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      u64 e = e0 + (LAYOUT_B ? off_b<K>(wave, r) : off_a<K>(wave, r)) + lane;
-      if (e < limit) store_one<NT>(p + e, from_f32<T>(v[r]));
-    }
+    for (int r = 0; r < R; ++r)
+      buf_store(rs, (LAYOUT_B ? off_b<K>(wave, r) : off_a<K>(wave, r)) + lane, v[r], (T*)nullptr);
   }
 }
 
