@@ -69,10 +69,9 @@ template <int K, bool ALL_FULL, class In>
 __device__ __forceinline__ void combine_parts(const In* __restrict__ x, u64 limit, u64 blk, int part, int wave, int lane,
                                               float (&v)[Geo<K>::R], const uint32_t (&sw)[Geo<K>::PARTS]) {
   constexpr int T = Geo<K>::T, HB = Geo<K>::HB, PARTS = Geo<K>::PARTS, R = Geo<K>::R;
-#pragma unroll
-  for (int q = 0; q < PARTS; ++q) {
-    float t[R];
-    load_tile<K, false, ALL_FULL>(x, ((blk << HB) + q) * T, limit, wave, lane, t);
+  // tile q+1 is in flight while tile q is signed and added
+  float ta[R], tb[R];
+  auto add_tile = [&](const float (&t)[R], int q) {
     const float c = part_coef(part, q);
     uint32_t w = sw[q];
     asm volatile("" : "+v"(w));   // keeps the lane masks of tile q from being formed before tile q is reached
@@ -81,7 +80,15 @@ __device__ __forceinline__ void combine_parts(const In* __restrict__ x, u64 limi
       const float ts = in_mask(mask_of_reg(w, r)) ? -t[r] : t[r];
       v[r] = q == 0 ? c * ts : __builtin_fmaf(c, ts, v[r]);
     }
-    __builtin_amdgcn_sched_barrier(0);   // one input tile at a time: bounds the live lane masks and tile registers
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  load_tile<K, false, ALL_FULL>(x, (blk << HB) * T, limit, wave, lane, ta);
+#pragma unroll
+  for (int q = 0; q < PARTS; q += 2) {
+    load_tile<K, false, ALL_FULL>(x, ((blk << HB) + q + 1) * T, limit, wave, lane, tb);
+    add_tile(ta, q);
+    if (q + 2 < PARTS) load_tile<K, false, ALL_FULL>(x, ((blk << HB) + q + 2) * T, limit, wave, lane, ta);
+    add_tile(tb, q + 1);
   }
 }
 

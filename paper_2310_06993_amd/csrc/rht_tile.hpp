@@ -52,7 +52,10 @@ struct Geo {
   static constexpr int KT = (K == 0) ? 10 : (K > 14 ? 14 : K);
   static constexpr int TL = KT;
   static constexpr int T = 1 << TL;
-  static constexpr int RL = (K != 0 && K >= OR_RL_FROM) ? OR_RL_BIG : 4;
+#ifndef OR_RL_TO
+#define OR_RL_TO 14
+#endif
+  static constexpr int RL = (K != 0 && K >= OR_RL_FROM && K <= OR_RL_TO) ? OR_RL_BIG : 4;
   static constexpr int R = 1 << RL;
   static constexpr int Q = TL - 6 - RL;          // wave bits
   static_assert(Q >= 0 && Q <= 4 && Q <= RL, "unsupported tile geometry");
@@ -343,6 +346,24 @@ __device__ __forceinline__ void load_tile(const T* __restrict__ p, u64 e0, u64 l
 #pragma unroll
     for (int r = 0; r < R; ++r)
       v[r] = buf_load(rs, (LAYOUT_B ? off_b<K>(wave, r) : off_a<K>(wave, r)) + lane, (const T*)nullptr);
+  }
+}
+
+// Registers R0 .. R0+NR-1 of a tile only (same addressing as load_tile).
+template <int K, bool LAYOUT_B, bool FULL, int R0, int NR, class T>
+__device__ __forceinline__ void load_tile_regs(const T* __restrict__ p, u64 e0, u64 limit, int wave, int lane,
+                                               float (&v)[NR]) {
+  if (FULL || e0 + Geo<K>::T <= limit) {
+    const T* q = p + e0;
+    const unsigned l = (unsigned)lane;
+#pragma unroll
+    for (int r = 0; r < NR; ++r)
+      v[r] = to_f32((q + (LAYOUT_B ? off_b<K>(wave, R0 + r) : off_a<K>(wave, R0 + r)))[l]);
+  } else {
+    const __amdgpu_buffer_rsrc_t rs = tile_rsrc(p, e0, limit);
+#pragma unroll
+    for (int r = 0; r < NR; ++r)
+      v[r] = buf_load(rs, (LAYOUT_B ? off_b<K>(wave, R0 + r) : off_a<K>(wave, R0 + r)) + lane, (const T*)nullptr);
   }
 }
 
