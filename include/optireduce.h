@@ -135,6 +135,37 @@ or_status or_fused_path_bf16(const uint16_t* grads, const uint32_t* masks, int N
                              int block_log2, uint64_t seed, uint64_t base_index, uint16_t* out, uint8_t* count_out,
                              void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- around the path: transform off, second-stage loss, loss monitoring, two-level aggregation ----
+ *
+ * or_finalize: the "averages" of Sec. 3.1.1 alone, mean = sum / count and 0 where count is 0 -- with
+ * or_masked_reduce this is the path with the Hadamard transform switched off (Sec. 3.2.1 enables it
+ * only above 2 % loss).  shard_len a multiple of 32; mean_out == sum is allowed for the fp32 form. */
+or_status or_finalize(const float* sum, const uint8_t* count, uint64_t shard_len, float* mean_out, void* stream);
+or_status or_finalize_bf16(const float* sum, const uint8_t* count, uint64_t shard_len, uint16_t* mean_out,
+                           void* stream);
+
+/* or_received_total: Sec. 3.4 monitors the gradient loss of every AllReduce to skip an update or halt.
+ * *total_out (device, 8-byte aligned) = sum of the counts = number of (worker, entry) arrivals; the
+ * loss fraction of the shard is 1 - total / (N * shard_len).  Exact integer. */
+or_status or_received_total(const uint8_t* count, uint64_t shard_len, uint64_t* total_out, void* stream);
+
+/* or_rht_decode_masked: decode after loss in the SECOND stage (Sec. 3.1.1: the owner broadcasts its
+ * aggregated shard over the same unreliable transport; Sec. 3.3: the transform spreads what is lost).
+ * mask: or_padded_len(n)/32 words, bit layout as for shards; an aggregated entry whose bit is clear
+ * never arrived, is never read and counts as zero.  Otherwise as or_rht_decode_at / _bf16. */
+or_status or_rht_decode_masked(const float* agg, const uint32_t* mask, uint64_t n, int block_log2, uint64_t seed,
+                               uint64_t base_index, float* out, void* stream);
+or_status or_rht_decode_masked_bf16(const float* agg, const uint32_t* mask, uint64_t n, int block_log2,
+                                    uint64_t seed, uint64_t base_index, uint16_t* out, void* stream);
+
+/* or_masked_reduce_pairs: second level of hierarchical 2D TAR (Sec. 3.1.2, Appendix A): every group
+ * has aggregated its members into a partial (sum, count) with or_masked_reduce; the partial
+ * aggregates of the G groups that arrived are combined, sums with sums and counts with counts.
+ * sums: [G][shard_len] fp32, counts: [G][shard_len] uint8, masks: [G][shard_len/32]; 1 <= G <= 255;
+ * the counts of one entry must not add up to more than 255. */
+or_status or_masked_reduce_pairs(const float* sums, const uint8_t* counts, const uint32_t* masks, int G,
+                                 uint64_t shard_len, float* sum_out, uint8_t* count_out, void* stream);
+
 /* or_fused_path_batched: or_fused_path / or_fused_path_bf16 for several buckets that share N,
  * block_log2 and element type, in as few launches as possible (up to 32 buckets per launch).  A DDP
  * bucket (Sec. 3.1.1 footnote: 25 MB by default) is only about a hundred tiles per shard, far too few

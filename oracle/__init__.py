@@ -58,6 +58,11 @@ def _load():
         for name in ("orc_masked_reduce_f32", "orc_masked_reduce_bf16"):
             getattr(L, name).argtypes = [_p, _p, _int, _u64, _p, _p]
         L.orc_finalize.argtypes = [_p, _p, _u64, _p]
+        for name in ("orc_rht_decode_masked_f32", "orc_rht_decode_masked_bf16"):
+            getattr(L, name).argtypes = [_p, _p, _u64, _int, _u64, _u64, _p]
+        L.orc_received_total.restype = _u64
+        L.orc_received_total.argtypes = [_p, _u64]
+        L.orc_masked_reduce_pairs.argtypes = [_p, _p, _p, _int, _u64, _p, _p]
         for name in ("orc_fused_path_f32", "orc_fused_path_bf16"):
             getattr(L, name).argtypes = [_p, _p, _int, _u64, _int, _u64, _u64, _p, _p]
         _lib = L
@@ -181,6 +186,42 @@ def rht_decode(agg, n: int, block_log2: int, seed: int, base_index: int = 0, out
         fn = "orc_rht_decode_f32"
     getattr(_load(), fn)(_ptr(a), n, block_log2, seed, base_index, _ptr(out))
     return out
+
+
+def rht_decode_masked(agg, mask, n: int, block_log2: int, seed: int, base_index: int = 0, out_dtype=None):
+    """Decode after second-stage loss (Sec. 3.1.1 broadcast stage, Sec. 3.3): aggregated entries whose
+    mask bit is clear never arrived and count as zero.  mask: padded_len(n)/32 uint32 words."""
+    a = _arr(agg, np.float32)
+    m = _arr(mask, np.uint32)
+    assert a.size == padded_len(n, block_log2) and m.size == a.size // 32
+    if out_dtype is not None and np.dtype(out_dtype) == np.uint16:
+        out = np.empty(n, np.uint16)
+        fn = "orc_rht_decode_masked_bf16"
+    else:
+        out = np.empty(n, np.float32)
+        fn = "orc_rht_decode_masked_f32"
+    getattr(_load(), fn)(_ptr(a), _ptr(m), n, block_log2, seed, base_index, _ptr(out))
+    return out
+
+
+def received_total(count) -> int:
+    """Sec. 3.4 loss monitoring: total number of (worker, entry) arrivals in the counts of one shard."""
+    c = _arr(count, np.uint8)
+    return int(_load().orc_received_total(_ptr(c), c.size))
+
+
+def masked_reduce_pairs(sums, counts, masks):
+    """Second level of hierarchical 2D TAR (Sec. 3.1.2, App. A): combine the groups' (sum, count)
+    partial aggregates that arrived.  sums [G, L] fp32, counts [G, L] uint8, masks [G, L/32]."""
+    s = _arr(sums, np.float32)
+    c = _arr(counts, np.uint8)
+    m = _arr(masks, np.uint32)
+    G, Ln = s.shape
+    assert c.shape == (G, Ln) and m.shape == (G, Ln // 32) and Ln % 32 == 0
+    total = np.empty(Ln, np.float32)
+    count = np.empty(Ln, np.uint8)
+    _load().orc_masked_reduce_pairs(_ptr(s), _ptr(c), _ptr(m), G, Ln, _ptr(total), _ptr(count))
+    return total, count
 
 
 def fused_path(grads, masks, block_log2: int, seed: int, base_index: int = 0):

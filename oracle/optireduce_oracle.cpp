@@ -247,6 +247,47 @@ void orc_rht_decode_bf16(const float* agg, uint64_t n, int k, uint64_t seed, uin
                  [&](uint64_t i, double v) { out[i] = float_to_bf16((float)v); });
 }
 
+// ---- second-stage loss (Sec. 3.1.1: the owner broadcasts its aggregated shard; Sec. 3.3: what is
+//      lost there is spread over the block by the decode).  An aggregated entry whose bit is clear
+//      never arrived and counts as zero; then decode as above.  mask: or_padded_len(n)/32 words.
+void orc_rht_decode_masked_f32(const float* agg, const uint32_t* mask, uint64_t n, int k, uint64_t seed,
+                               uint64_t base_index, float* out) {
+  decode_generic(n, k, seed, base_index, [&](uint64_t i) { return mask_bit(mask, i) ? (double)agg[i] : 0.0; },
+                 [&](uint64_t i, double v) { out[i] = (float)v; });
+}
+void orc_rht_decode_masked_bf16(const float* agg, const uint32_t* mask, uint64_t n, int k, uint64_t seed,
+                                uint64_t base_index, uint16_t* out) {
+  decode_generic(n, k, seed, base_index, [&](uint64_t i) { return mask_bit(mask, i) ? (double)agg[i] : 0.0; },
+                 [&](uint64_t i, double v) { out[i] = float_to_bf16((float)v); });
+}
+
+// ---- loss monitoring (Sec. 3.4): how many (worker, entry) pairs arrived in this AllReduce;
+//      the loss fraction is 1 - total / (N * L).
+uint64_t orc_received_total(const uint8_t* count, uint64_t L) {
+  uint64_t t = 0;
+  for (uint64_t e = 0; e < L; ++e) t += count[e];
+  return t;
+}
+
+// ---- second level of the hierarchical 2D scheme (Sec. 3.1.2, Appendix A): each group has already
+//      aggregated its members into (sum, count); the partial aggregates of the groups that arrived
+//      are combined, sums with sums and counts with counts.
+void orc_masked_reduce_pairs(const float* sums, const uint8_t* counts, const uint32_t* masks, int G, uint64_t L,
+                             float* sum_out, uint8_t* count_out) {
+  const uint64_t words = L / 32;
+  for (uint64_t e = 0; e < L; ++e) {
+    double acc = 0.0;
+    unsigned cnt = 0;
+    for (int g = 0; g < G; ++g)
+      if (mask_bit(masks + (uint64_t)g * words, e)) {
+        acc += (double)sums[(uint64_t)g * L + e];
+        cnt += counts[(uint64_t)g * L + e];
+      }
+    sum_out[e] = (float)acc;
+    count_out[e] = (uint8_t)cnt;
+  }
+}
+
 // ---- the whole path for one shard held by one node, as the composition of the
 //      steps above with every memory-boundary rounding kept:
 //      raw slices of N workers -> encode each -> masked sum/count -> mean -> decode.

@@ -45,6 +45,12 @@ _SIGS = {
     "or_fused_path": (_int, [_p, _p, _int, _u64, _int, _u64, _u64, _p, _p, _p, _sz, _p]),
     "or_fused_path_bf16": (_int, [_p, _p, _int, _u64, _int, _u64, _u64, _p, _p, _p, _sz, _p]),
     "or_fused_path_batched": (_int, [_p, _int, _int, _int, _int, _p, _sz, _p]),
+    "or_finalize": (_int, [_p, _p, _u64, _p, _p]),
+    "or_finalize_bf16": (_int, [_p, _p, _u64, _p, _p]),
+    "or_received_total": (_int, [_p, _u64, _p, _p]),
+    "or_rht_decode_masked": (_int, [_p, _p, _u64, _int, _u64, _u64, _p, _p]),
+    "or_rht_decode_masked_bf16": (_int, [_p, _p, _u64, _int, _u64, _u64, _p, _p]),
+    "or_masked_reduce_pairs": (_int, [_p, _p, _p, _int, _u64, _p, _p, _p]),
 }
 
 
@@ -196,3 +202,32 @@ def or_fused_path_batched(buckets, n_buckets, N, block_log2, bf16, workspace=Non
     w, wb = _ws(workspace)
     _check(lib.or_fused_path_batched(C.cast(buckets, _p), n_buckets, N, block_log2, int(bool(bf16)), w, wb,
                                      _stream(stream)), "or_fused_path_batched")
+
+
+def or_finalize(total, count, shard_len, mean_out, stream=None):
+    _check(lib.or_finalize(_ptr(total), _ptr(count), shard_len, _ptr(mean_out), _stream(stream)), "or_finalize")
+
+
+def or_finalize_bf16(total, count, shard_len, mean_out, stream=None):
+    _check(lib.or_finalize_bf16(_ptr(total), _ptr(count), shard_len, _ptr(mean_out), _stream(stream)),
+           "or_finalize_bf16")
+
+
+def or_received_total(count, shard_len, total_out, stream=None):
+    """total_out: a one-element int64 device tensor."""
+    _check(lib.or_received_total(_ptr(count), shard_len, _ptr(total_out), _stream(stream)), "or_received_total")
+
+
+def or_rht_decode_masked(agg, mask, n, block_log2, seed, base_index, out, stream=None):
+    _check(lib.or_rht_decode_masked(_ptr(agg), _ptr(mask), n, block_log2, seed, base_index, _ptr(out),
+                                    _stream(stream)), "or_rht_decode_masked")
+
+
+def or_rht_decode_masked_bf16(agg, mask, n, block_log2, seed, base_index, out, stream=None):
+    _check(lib.or_rht_decode_masked_bf16(_ptr(agg), _ptr(mask), n, block_log2, seed, base_index, _ptr(out),
+                                         _stream(stream)), "or_rht_decode_masked_bf16")
+
+
+def or_masked_reduce_pairs(sums, counts, masks, G, shard_len, sum_out, count_out, stream=None):
+    _check(lib.or_masked_reduce_pairs(_ptr(sums), _ptr(counts), _ptr(masks), G, shard_len, _ptr(sum_out),
+                                      _ptr(count_out), _stream(stream)), "or_masked_reduce_pairs")

@@ -55,6 +55,8 @@ OR_SPLIT_LAUNCHER(dec_f32, (k_decode<K, float, false, true>), (k_decode<K, float
 OR_SPLIT_LAUNCHER(dec_bf16, (k_decode<K, bf16_t, false, true>), (k_decode<K, bf16_t, false, false>))
 OR_SPLIT_LAUNCHER(fdec_f32, (k_decode<K, float, true, true>), (k_decode<K, float, true, false>))
 OR_SPLIT_LAUNCHER(fdec_bf16, (k_decode<K, bf16_t, true, true>), (k_decode<K, bf16_t, true, false>))
+OR_SPLIT_LAUNCHER(mdec_f32, (k_decode<K, float, false, true, true>), (k_decode<K, float, false, false, true>))
+OR_SPLIT_LAUNCHER(mdec_bf16, (k_decode<K, bf16_t, false, true, true>), (k_decode<K, bf16_t, false, false, true>))
 #if OR_K <= 14
 OR_LAUNCHER(rdec_f32, (k_reduce_decode<K, float, float>))
 OR_LAUNCHER(rdec_bf16, (k_reduce_decode<K, bf16_t, bf16_t>))
@@ -72,7 +74,7 @@ OR_LAUNCHER(fus_bf16, (k_fused<K, bf16_t, false>))
 #define OR_CAT2(a, b) a##b
 #define OR_CAT(a, b) OR_CAT2(a, b)
 extern const KernelTable OR_CAT(or_kernel_table_, OR_K) = {
-    G::TL, enc_f32, enc_bf16, dec_f32, dec_bf16, fdec_f32, fdec_bf16,
+    G::TL, enc_f32, enc_bf16, dec_f32, dec_bf16, fdec_f32, fdec_bf16, mdec_f32, mdec_bf16,
 #if OR_K <= 14
     rdec_f32, rdec_bf16,
 #else

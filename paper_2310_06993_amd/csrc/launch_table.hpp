@@ -35,6 +35,7 @@ struct KernelTable {
   launch_fn encode_f32, encode_bf16;
   launch_fn decode_f32, decode_bf16;                    // input: fp32 mean
   launch_fn finalize_decode_f32, finalize_decode_bf16;  // input: fp32 sum + u8 count
+  launch_fn decode_masked_f32, decode_masked_bf16;      // input: fp32 mean + received bits of the second stage
   launch_fn reduce_decode_f32, reduce_decode_bf16;      // null when a block spans several tiles
   launch_fn fused_f32, fused_bf16;                      // decode fused in when a block is one tile, else stops at the mean
   batch_fn fused_batched_f32, fused_batched_bf16;       // null when a block spans several tiles

@@ -84,12 +84,15 @@ __global__ __launch_bounds__(256) void k_masked_reduce(const Wire* __restrict__ 
       cnt[j] += got ? 1u : 0u;
     }
   }
+  // nontemporal: the results are not read again here and reads dominate the traffic
   typedef float f4 __attribute__((ext_vector_type(4)));
 #pragma unroll
-  for (int j = 0; j < VEC; j += 4) *(f4*)(sum_out + e + j) = f4{acc[j], acc[j + 1], acc[j + 2], acc[j + 3]};
+  for (int j = 0; j < VEC; j += 4)
+    __builtin_nontemporal_store(f4{acc[j], acc[j + 1], acc[j + 2], acc[j + 3]}, (f4*)(sum_out + e + j));
 #pragma unroll
   for (int j = 0; j < VEC; j += 4)
-    *(uint32_t*)(count_out + e + j) = cnt[j] | (cnt[j + 1] << 8) | (cnt[j + 2] << 16) | (cnt[j + 3] << 24);
+    __builtin_nontemporal_store(cnt[j] | (cnt[j + 1] << 8) | (cnt[j + 2] << 16) | (cnt[j + 3] << 24),
+                                (uint32_t*)(count_out + e + j));
 }
 
 template <class Wire, int VEC>
@@ -101,6 +104,86 @@ hipError_t launch_masked_reduce(const void* shards, const uint32_t* masks, int N
   if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
   return orhost::launch_kernel(k_masked_reduce<Wire, VEC>, dim3((unsigned)blocks), dim3(256), s, pos,
                                (const Wire*)shards, masks, N, L, sum_out, count_out);
+}
+
+// ------------------------------------------------------------------ small streaming kernels
+// mean = sum / count, 0 where count is 0 (Sec. 3.1.1 "averages" over what arrived); 4 entries per lane
+template <class Out>
+__global__ __launch_bounds__(256) void k_finalize(const float* __restrict__ sum, const uint8_t* __restrict__ count, u64 L,
+                                                  Out* __restrict__ mean) {
+  const u64 e = ((u64)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (e >= L) return;
+  typedef float f4 __attribute__((ext_vector_type(4)));
+  const f4 s4 = *(const f4*)(sum + e);
+  const uint32_t c4 = *(const uint32_t*)(count + e);
+  float m[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float c = (float)((c4 >> (8 * j)) & 0xFFu);
+    m[j] = c > 0.0f ? s4[j] / c : 0.0f;
+  }
+  if constexpr (sizeof(Out) == 4) {
+    *(f4*)(mean + e) = f4{m[0], m[1], m[2], m[3]};
+  } else {
+    typedef uint16_t h4 __attribute__((ext_vector_type(4)));
+    h4 h;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) h[j] = __builtin_bit_cast(uint16_t, (__bf16)m[j]);
+    *(h4*)(mean + e) = h;
+  }
+}
+
+__global__ void k_zero_u64(unsigned long long* p) { *p = 0; }
+
+// Sec. 3.4 loss monitoring: total of the received counts of a shard (16 counts per lane, byte sums
+// with v_sad_u8, one 64-bit atomic per wavefront)
+__global__ __launch_bounds__(256) void k_received_total(const uint8_t* __restrict__ count, u64 L,
+                                                        unsigned long long* __restrict__ total) {
+  typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+  uint32_t acc = 0;
+  for (u64 e = ((u64)blockIdx.x * 256 + threadIdx.x) * 16; e < L; e += (u64)gridDim.x * 256 * 16) {
+    if (e + 16 <= L) {
+      const u4 c = *(const u4*)(count + e);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_sad_u8(c[j], 0u, acc);
+    } else {
+      for (u64 i = e; i < L; ++i) acc += count[i];
+    }
+  }
+  unsigned long long w = acc;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) w += __shfl_xor(w, o, 64);
+  if ((threadIdx.x & 63) == 0 && w) atomicAdd(total, w);
+}
+
+// Second level of hierarchical 2D TAR (Sec. 3.1.2, App. A): sums with sums, counts with counts, over
+// the groups whose partial aggregate arrived; 4 entries per lane
+__global__ __launch_bounds__(256) void k_masked_reduce_pairs(const float* __restrict__ sums,
+                                                             const uint8_t* __restrict__ counts,
+                                                             const uint32_t* __restrict__ masks, int G, u64 L,
+                                                             float* __restrict__ sum_out,
+                                                             uint8_t* __restrict__ count_out) {
+  const u64 e = ((u64)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (e >= L) return;
+  typedef float f4 __attribute__((ext_vector_type(4)));
+  const u64 words = L >> 5;
+  const int sh = (int)(e & 31);
+  float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  uint32_t cnt[4] = {0, 0, 0, 0};
+  for (int g = 0; g < G; ++g) {
+    const f4 x = *(const f4*)(sums + (u64)g * L + e);
+    const uint32_t c4 = *(const uint32_t*)(counts + (u64)g * L + e);
+    const uint32_t m = masks[(u64)g * words + (e >> 5)] >> sh;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const bool got = (m >> j) & 1u;
+      acc[j] += got ? x[j] : 0.0f;
+      cnt[j] += got ? ((c4 >> (8 * j)) & 0xFFu) : 0u;
+    }
+  }
+  __builtin_nontemporal_store(f4{acc[0], acc[1], acc[2], acc[3]}, (f4*)(sum_out + e));
+  __builtin_nontemporal_store((cnt[0] & 0xFFu) | ((cnt[1] & 0xFFu) << 8) | ((cnt[2] & 0xFFu) << 16) | (cnt[3] << 24),
+                              (uint32_t*)(count_out + e));
 }
 
 // ------------------------------------------------------------------ checks
@@ -175,7 +258,7 @@ or_status encode_impl(const T* grad, u64 n, int k, u64 seed, u64 base, T* out, v
 
 template <class T>
 or_status decode_impl(const float* agg, const uint8_t* count, bool finalize, u64 n, int k, u64 seed, u64 base, T* out,
-                      void* stream, bool bf16) {
+                      void* stream, bool bf16, const uint32_t* stage2_mask = nullptr, bool masked = false) {
   DisarmOnExit disarm;
   const u64 n_pad = valid_k(k) ? padded(n, k) : 0;
   if (or_status s = check_transform(agg, n_pad, 4, out, n, sizeof(T), k, base)) return s;
@@ -184,14 +267,21 @@ or_status decode_impl(const float* agg, const uint8_t* count, bool finalize, u64
     if (!count) return OR_ERR_NULL;
     if (ranges_overlap(count, n_pad, out, n * sizeof(T))) return OR_ERR_SHAPE;
   }
+  if (masked) {
+    if (!stage2_mask) return OR_ERR_NULL;
+    if (!aligned(stage2_mask, 4)) return OR_ERR_ALIGN;
+    if (ranges_overlap(stage2_mask, n_pad / 8, out, n * sizeof(T))) return OR_ERR_SHAPE;
+  }
   const orhost::KernelTable* t = orhost::table_for_class(class_of(k));
   PathArgs a = {};
-  a.in = agg; a.count_in = count; a.out = out; a.n = n; a.n_pad = n_pad; a.seed = seed; a.base = base; a.k = k;
+  a.in = agg; a.count_in = count; a.masks = stage2_mask; a.out = out; a.n = n; a.n_pad = n_pad; a.seed = seed;
+  a.base = base; a.k = k;
   a.scale = scale_of(k);
   const u64 units = (n_pad + ((u64)1 << t->tile_log2) - 1) >> t->tile_log2;
   a.unit0 = full_units(n, k, t->tile_log2);
-  orhost::launch_fn f = finalize ? (bf16 ? t->finalize_decode_bf16 : t->finalize_decode_f32)
-                                 : (bf16 ? t->decode_bf16 : t->decode_f32);
+  orhost::launch_fn f = masked     ? (bf16 ? t->decode_masked_bf16 : t->decode_masked_f32)
+                        : finalize ? (bf16 ? t->finalize_decode_bf16 : t->finalize_decode_f32)
+                                   : (bf16 ? t->decode_bf16 : t->decode_f32);
   return finish(f(a, units, (hipStream_t)stream, orhost::LAUNCH_ONLY));
 }
 
@@ -301,6 +391,61 @@ or_status path_impl(bool fused, const T* in, const uint32_t* masks, int N, u64 L
   DisarmOnExit disarm;
   if (or_status s = check_path(in, masks, N, L, k, base, out, count_out, ws, ws_bytes, sizeof(T))) return s;
   return run_path<T>(fused, in, masks, N, L, k, seed, base, out, count_out, ws, stream, bf16);
+}
+
+template <class Out>
+or_status finalize_impl(const float* sum, const uint8_t* count, u64 L, Out* mean, void* stream) {
+  DisarmOnExit disarm;
+  if (L % 32 || L > ((u64)1 << 40)) return OR_ERR_SHAPE;
+  if (L == 0) return OR_OK;
+  if (!sum || !count || !mean) return OR_ERR_NULL;
+  if (!aligned(sum, 16) || !aligned(count, 4) || !aligned(mean, 16)) return OR_ERR_ALIGN;
+  if (ranges_overlap(mean, L * sizeof(Out), count, L)) return OR_ERR_SHAPE;
+  if (ranges_overlap(mean, L * sizeof(Out), sum, L * 4) && !((const void*)mean == (const void*)sum && sizeof(Out) == 4))
+    return OR_ERR_SHAPE;
+  const u64 blocks = (L / 4 + 255) / 256;
+  if (blocks > 0x7FFFFFFFull) return OR_ERR_SHAPE;
+  return finish(orhost::launch_kernel(k_finalize<Out>, dim3((unsigned)blocks), dim3(256), (hipStream_t)stream,
+                                      orhost::LAUNCH_ONLY, sum, count, L, mean));
+}
+
+or_status received_total_impl(const uint8_t* count, u64 L, unsigned long long* total, void* stream) {
+  DisarmOnExit disarm;
+  if (L > ((u64)1 << 40)) return OR_ERR_SHAPE;
+  if (!total) return OR_ERR_NULL;
+  if (!aligned(total, 8)) return OR_ERR_ALIGN;
+  if (L && !count) return OR_ERR_NULL;
+  if (L && !aligned(count, 16)) return OR_ERR_ALIGN;
+  if (L && ranges_overlap(total, 8, count, L)) return OR_ERR_SHAPE;
+  hipStream_t s = (hipStream_t)stream;
+  if (hipError_t e = orhost::launch_kernel(k_zero_u64, dim3(1), dim3(1), s, L ? orhost::LAUNCH_FIRST : orhost::LAUNCH_ONLY,
+                                           total))
+    return finish(e);
+  if (L == 0) return OR_OK;
+  u64 blocks = (L / 16 + 255) / 256;
+  if (blocks > 4096) blocks = 4096;   // grid-stride: a few atomics per CU are enough
+  if (blocks == 0) blocks = 1;
+  return finish(orhost::launch_kernel(k_received_total, dim3((unsigned)blocks), dim3(256), s, orhost::LAUNCH_LAST, count, L,
+                                      total));
+}
+
+or_status pairs_impl(const float* sums, const uint8_t* counts, const uint32_t* masks, int G, u64 L, float* sum_out,
+                     uint8_t* count_out, void* stream) {
+  DisarmOnExit disarm;
+  if (or_status s = check_reduce(sums, masks, G, L, 4)) return s;
+  if (L == 0) return OR_OK;
+  if (!counts || !sum_out || !count_out) return OR_ERR_NULL;
+  if (!aligned(counts, 4) || !aligned(sum_out, 16) || !aligned(count_out, 4)) return OR_ERR_ALIGN;
+  const u64 sb = (u64)G * L * 4, cb = (u64)G * L, mb = (u64)G * (L / 8);
+  if (ranges_overlap(sum_out, L * 4, sums, sb) || ranges_overlap(sum_out, L * 4, counts, cb) ||
+      ranges_overlap(sum_out, L * 4, masks, mb) || ranges_overlap(count_out, L, sums, sb) ||
+      ranges_overlap(count_out, L, counts, cb) || ranges_overlap(count_out, L, masks, mb) ||
+      ranges_overlap(sum_out, L * 4, count_out, L))
+    return OR_ERR_SHAPE;
+  const u64 blocks = (L / 4 + 255) / 256;
+  if (blocks > 0x7FFFFFFFull) return OR_ERR_SHAPE;
+  return finish(orhost::launch_kernel(k_masked_reduce_pairs, dim3((unsigned)blocks), dim3(256), (hipStream_t)stream,
+                                      orhost::LAUNCH_ONLY, sums, counts, masks, G, L, sum_out, count_out));
 }
 
 or_status batched_impl(const or_bucket* buckets, int n, int N, int k, bool bf16, void* ws, size_t ws_bytes, void* stream) {
@@ -443,6 +588,29 @@ or_status or_fused_path_bf16(const uint16_t* grads, const uint32_t* masks, int N
                              void* workspace, size_t workspace_bytes, void* stream) {
   return path_impl<uint16_t>(true, grads, masks, N, shard_len, block_log2, seed, base_index, out, count_out, workspace,
                              workspace_bytes, stream, true);
+}
+
+or_status or_finalize(const float* sum, const uint8_t* count, uint64_t shard_len, float* mean_out, void* stream) {
+  return finalize_impl<float>(sum, count, shard_len, mean_out, stream);
+}
+or_status or_finalize_bf16(const float* sum, const uint8_t* count, uint64_t shard_len, uint16_t* mean_out,
+                           void* stream) {
+  return finalize_impl<uint16_t>(sum, count, shard_len, mean_out, stream);
+}
+or_status or_received_total(const uint8_t* count, uint64_t shard_len, uint64_t* total_out, void* stream) {
+  return received_total_impl(count, shard_len, (unsigned long long*)total_out, stream);
+}
+or_status or_rht_decode_masked(const float* agg, const uint32_t* mask, uint64_t n, int block_log2, uint64_t seed,
+                               uint64_t base_index, float* out, void* stream) {
+  return decode_impl<float>(agg, nullptr, false, n, block_log2, seed, base_index, out, stream, false, mask, true);
+}
+or_status or_rht_decode_masked_bf16(const float* agg, const uint32_t* mask, uint64_t n, int block_log2,
+                                    uint64_t seed, uint64_t base_index, uint16_t* out, void* stream) {
+  return decode_impl<uint16_t>(agg, nullptr, false, n, block_log2, seed, base_index, out, stream, true, mask, true);
+}
+or_status or_masked_reduce_pairs(const float* sums, const uint8_t* counts, const uint32_t* masks, int G,
+                                 uint64_t shard_len, float* sum_out, uint8_t* count_out, void* stream) {
+  return pairs_impl(sums, counts, masks, G, shard_len, sum_out, count_out, stream);
 }
 
 or_status or_fused_path_batched(const or_bucket* buckets, int n_buckets, int N, int block_log2, int bf16,

@@ -139,8 +139,10 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_encode(PathArgs a) {
 }
 
 // Mean tile (layout B) for decode: either the mean itself, or sum / count with 0 where count is 0
-// (the "averages" of Sec. 3.1.1 taken over the entries that arrived).
-template <int K, bool FINALIZE, bool FULL>
+// (the "averages" of Sec. 3.1.1 taken over the entries that arrived).  MASKED: second-stage loss
+// (the broadcast of the aggregated shard, Sec. 3.1.1): entries whose bit in a.masks is clear never
+// arrived and count as zero.
+template <int K, bool FINALIZE, bool FULL, bool MASKED>
 __device__ __forceinline__ void load_mean_tile(const PathArgs& a, u64 tile, int wave, int lane,
                                                float (&v)[Geo<K>::R]) {
   constexpr int T = Geo<K>::T, R = Geo<K>::R;
@@ -151,10 +153,17 @@ __device__ __forceinline__ void load_mean_tile(const PathArgs& a, u64 tile, int 
 #pragma unroll
     for (int r = 0; r < R; ++r) v[r] = c[r] > 0.0f ? v[r] / c[r] : 0.0f;
   }
+  if constexpr (MASKED) {
+    const uint32_t w = load_mask_words<K, FULL>(a.masks, tile * T, a.n_pad, mask_word_offset<K>(wave, lane));
+    if (!all_arrived(w)) {
+#pragma unroll
+      for (int r = 0; r < R; ++r) v[r] = in_mask(mask_of_reg(w, r)) ? v[r] : 0.0f;
+    }
+  }
 }
 
 // Sec. 3.3 / Sec. 4 decode: out = D B^(-1/2) H mean, first n entries kept.
-template <int K, class Out, bool FINALIZE, bool FULL>
+template <int K, class Out, bool FINALIZE, bool FULL, bool MASKED = false>
 __global__ __launch_bounds__(Geo<K>::THREADS) void k_decode(PathArgs a) {
   constexpr int T = Geo<K>::T, HB = Geo<K>::HB, PARTS = Geo<K>::PARTS, R = Geo<K>::R;
   __shared__ float xbuf[Geo<K>::Q > 0 ? T : 1];
@@ -164,7 +173,7 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_decode(PathArgs a) {
   if (none) return;
   float v[R];
   if constexpr (PARTS == 1) {
-    load_mean_tile<K, FINALIZE, FULL>(a, unit, wave, lane, v);
+    load_mean_tile<K, FINALIZE, FULL, MASKED>(a, unit, wave, lane, v);
   } else {
     const u64 blk = unit >> HB;
     const int part = (int)(unit & (PARTS - 1));
@@ -172,7 +181,7 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_decode(PathArgs a) {
     for (int r = 0; r < R; ++r) v[r] = 0.0f;
     for (int q = 0; q < PARTS; ++q) {
       float t[R];
-      load_mean_tile<K, FINALIZE, FULL>(a, (blk << HB) + q, wave, lane, t);
+      load_mean_tile<K, FINALIZE, FULL, MASKED>(a, (blk << HB) + q, wave, lane, t);
       const float c = part_coef(part, q);
 #pragma unroll
       for (int r = 0; r < R; ++r) v[r] = __builtin_fmaf(c, t[r], v[r]);

@@ -338,3 +338,68 @@ def test_bf16_path_rounds_only_at_boundaries(orc):
     got = orc.bf16_to_float(out).astype(np.float64)
     assert np.linalg.norm(got - want) / np.linalg.norm(want) < 4e-3   # one bf16 rounding of the output
     assert np.array_equal(count, recv.sum(axis=0).astype(np.uint8))
+
+
+# ------------------------------------------------------------------ second-stage loss, monitoring, two levels
+def test_decode_masked_is_decode_of_zero_filled(orc):
+    k, seed = 8, 13
+    B = 1 << k
+    n = 3 * B - 7
+    rng = np.random.default_rng(31)
+    agg = rng.standard_normal(orc.padded_len(n, k)).astype(np.float32)
+    recv = rng.random(agg.size) > 0.05
+    got = orc.rht_decode_masked(agg, pack_mask(recv[None, :])[0], n, k, seed, 2 * B)
+    H = dense_hadamard(B) / np.sqrt(B)
+    s = signs_pm1(orc, seed, 2 * B, agg.size)
+    want = s * (H @ np.where(recv, agg.astype(np.float64), 0.0).reshape(-1, B).T).T.reshape(-1)
+    np.testing.assert_allclose(got, want[:n], rtol=0, atol=2e-6)
+    # all arrived: the plain decode, bit for bit
+    full = np.full(agg.size // 32, 0xFFFFFFFF, np.uint32)
+    assert np.array_equal(orc.rht_decode_masked(agg, full, n, k, seed, 2 * B), orc.rht_decode(agg, n, k, seed, 2 * B))
+    # one aggregated entry lost in the broadcast: same magnitude |a_j|/sqrt(B) everywhere in its block
+    one = full.copy()
+    j = B + 5
+    one[j // 32] &= ~np.uint32(1 << (j % 32))
+    err = orc.rht_decode_masked(agg, one, agg.size, k, seed, 0).astype(np.float64) - \
+        orc.rht_decode(agg, agg.size, k, seed, 0).astype(np.float64)
+    assert np.allclose(np.abs(err[B:2 * B]), abs(agg[j]) / np.sqrt(B), rtol=1e-4)
+    assert not err[:B].any() and not err[2 * B:].any()
+
+
+def test_received_total_and_loss_fraction(orc):
+    rng = np.random.default_rng(32)
+    N, L = 6, 32 * 50
+    recv = rng.random((N, L)) > 0.1
+    _, count = orc.masked_reduce(rng.standard_normal((N, L)).astype(np.float32), pack_mask(recv))
+    assert orc.received_total(count) == int(recv.sum())
+    assert orc.received_total(np.full(1000, 255, np.uint8)) == 255000
+    assert orc.received_total(np.zeros(0, np.uint8)) == 0
+
+
+def test_two_level_reduce_equals_one_level(orc):
+    # Sec. 3.1.2: aggregate inside each group, then across groups.  With every group aggregate
+    # delivered this is the one-level aggregation (sums exactly representable here); a group aggregate
+    # lost at the second level is the same as all of that group's members lost at that entry.
+    rng = np.random.default_rng(33)
+    G, M, L = 4, 3, 32 * 20
+    x = rng.integers(-8, 9, (G * M, L)).astype(np.float32)
+    recv = rng.random((G * M, L)) > 0.2
+    masks = pack_mask(recv)
+    sums = np.empty((G, L), np.float32)
+    counts = np.empty((G, L), np.uint8)
+    for g in range(G):
+        sums[g], counts[g] = orc.masked_reduce(x[g * M:(g + 1) * M], masks[g * M:(g + 1) * M])
+    all_ones = np.full((G, L // 32), 0xFFFFFFFF, np.uint32)
+    t2, c2 = orc.masked_reduce_pairs(sums, counts, all_ones)
+    t1, c1 = orc.masked_reduce(x, masks)
+    assert np.array_equal(t2, t1) and np.array_equal(c2, c1)
+    recv2 = rng.random((G, L)) > 0.25
+    t2, c2 = orc.masked_reduce_pairs(sums, counts, pack_mask(recv2))
+    t1, c1 = orc.masked_reduce(x, pack_mask(recv & np.repeat(recv2, M, axis=0)))
+    assert np.array_equal(t2, t1) and np.array_equal(c2, c1)
+    # hand-sized case: two groups, sums (3, 10) and counts (2, 1); only the second arrives at entry 0
+    s = np.zeros((2, 32), np.float32); c = np.zeros((2, 32), np.uint8)
+    s[:, 0] = [3, 10]; c[:, 0] = [2, 1]
+    m = np.zeros((2, 1), np.uint32); m[1, 0] = 1
+    t, cc = orc.masked_reduce_pairs(s, c, m)
+    assert t[0] == 10 and cc[0] == 1 and not t[1:].any() and not cc[1:].any()

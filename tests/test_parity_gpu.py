@@ -378,3 +378,90 @@ def test_batched_buckets_equal_single_calls(b, orc, k, kind):
     assert e.value.status == 4
     torch.cuda.synchronize()
     assert bool((items[0][2].float() == 5.0).all())
+
+
+# ------------------------------------------------------------------ around the path
+@pytest.mark.parametrize("N,L", [(4, 32 * 5), (8, 4096 * 3 + 64)])
+def test_finalize_and_transform_off_path(b, orc, N, L):
+    rng = np.random.default_rng(L)
+    x = rng.standard_normal((N, L)).astype(np.float32)
+    recv = rng.random((N, L)) > 0.3
+    recv[:, 7] = False
+    masks = pack_mask_np(recv)
+    total = torch.empty(L, device=dev())
+    count = torch.empty(L, dtype=torch.uint8, device=dev())
+    b.or_masked_reduce(torch.from_numpy(x).to(dev()), masks_to_dev(masks), N, L, total, count)
+    mean = torch.full((L,), float("nan"), device=dev())
+    b.or_finalize(total, count, L, mean)
+    ws, wc = orc.masked_reduce(x, masks)
+    want = orc.finalize(ws, wc)
+    assert rel_l2(to_np(mean), want) <= TOL["f32"] and float(mean[7]) == 0.0
+    meanh = torch.zeros(L, dtype=torch.bfloat16, device=dev())
+    b.or_finalize_bf16(total, count, L, meanh)
+    assert rel_l2(to_np(meanh), want) <= TOL["bf16"]
+    b.or_finalize(total, count, L, total)          # in place
+    assert torch.equal(total, mean)
+    # loss monitoring: exact
+    tot = torch.full((1,), -1, dtype=torch.int64, device=dev())
+    b.or_received_total(count, L, tot)
+    assert int(tot.item()) == orc.received_total(wc) == int(recv.sum())
+
+
+def test_received_total_large_and_empty(b):
+    L = 32 * 100_003
+    c = torch.randint(0, 256, (L,), dtype=torch.uint8, device=dev(), generator=torch.Generator(device=dev()).manual_seed(1))
+    tot = torch.zeros(1, dtype=torch.int64, device=dev())
+    b.or_received_total(c, L, tot)
+    assert int(tot.item()) == int(c.to(torch.int64).sum().item())
+    b.or_received_total(c, 0, tot)
+    assert int(tot.item()) == 0
+
+
+@pytest.mark.parametrize("k", [5, 10, 12, 14, 16])
+def test_decode_masked(b, orc, k):
+    B = 1 << k
+    n = _sizes(k)[0]
+    n_pad = b.or_padded_len(n, k)
+    rng = np.random.default_rng(400 + k)
+    agg = rng.standard_normal(n_pad).astype(np.float32)
+    recv = rng.random(n_pad) > 0.05
+    recv[64:128] = False
+    mask = pack_mask_np(recv[None, :])[0]
+    seed, base = 77, 2 * max(B, 128)
+    poisoned = np.where(recv, agg, np.nan).astype(np.float32)     # lost entries are never read
+    out = torch.empty(n, device=dev())
+    b.or_rht_decode_masked(torch.from_numpy(poisoned).to(dev()), masks_to_dev(mask[None, :])[0], n, k, seed, base, out)
+    assert rel_l2(to_np(out), orc.rht_decode_masked(agg, mask, n, k, seed, base)) <= TOL["f32"]
+    outh = torch.empty(n, dtype=torch.bfloat16, device=dev())
+    b.or_rht_decode_masked_bf16(torch.from_numpy(poisoned).to(dev()), masks_to_dev(mask[None, :])[0], n, k, seed, base, outh)
+    assert rel_l2(to_np(outh), orc.rht_decode_masked(agg, mask, n, k, seed, base, out_dtype=np.uint16)) <= TOL["bf16"]
+    full = torch.full((n_pad // 32,), -1, dtype=torch.int32, device=dev())
+    out2 = torch.empty(n, device=dev())
+    b.or_rht_decode_masked(torch.from_numpy(agg).to(dev()), full, n, k, seed, base, out2)
+    out3 = torch.empty(n, device=dev())
+    b.or_rht_decode_at(torch.from_numpy(agg).to(dev()), n, k, seed, base, out3)
+    assert torch.equal(out2, out3)
+
+
+@pytest.mark.parametrize("G,M,L", [(2, 2, 64), (4, 4, 32 * 300 + 32), (16, 3, 4096)])
+def test_two_level_reduce(b, orc, G, M, L):
+    rng = np.random.default_rng(G * 100 + M)
+    x = rng.standard_normal((G * M, L)).astype(np.float32)
+    recv = rng.random((G * M, L)) > 0.2
+    masks = pack_mask_np(recv)
+    sums = torch.empty((G, L), device=dev())
+    counts = torch.empty((G, L), dtype=torch.uint8, device=dev())
+    xd, md = torch.from_numpy(x).to(dev()), masks_to_dev(masks)
+    for g in range(G):
+        b.or_masked_reduce(xd[g * M:(g + 1) * M], md[g * M:(g + 1) * M], M, L, sums[g], counts[g])
+    recv2 = rng.random((G, L)) > 0.15
+    m2 = pack_mask_np(recv2)
+    total = torch.empty(L, device=dev())
+    count = torch.empty(L, dtype=torch.uint8, device=dev())
+    sums_poisoned = torch.where(torch.from_numpy(recv2).to(dev()), sums, torch.full_like(sums, float("nan")))
+    b.or_masked_reduce_pairs(sums_poisoned, counts, masks_to_dev(m2), G, L, total, count)
+    ws, wc = orc.masked_reduce_pairs(to_np(sums), to_np(counts), m2)
+    assert np.array_equal(to_np(count), wc) and rel_l2(to_np(total), ws) <= TOL["f32"]
+    # the same as one level with a lost group = all its members lost (counts exactly, sums to rounding)
+    w1, c1 = orc.masked_reduce(x, pack_mask_np(recv & np.repeat(recv2, M, axis=0)))
+    assert np.array_equal(to_np(count), c1) and rel_l2(to_np(total), w1) <= TOL["f32"]
