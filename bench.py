@@ -128,6 +128,44 @@ def kernel_only_seconds(b, cfg, L, sets, launches=32):
     return t
 
 
+def time_three_calls(wl, b, cfg, sets, iters=20):
+    """The same shard through the separate calls: encode (this node's own full gradient, N*L entries),
+    masked reduce of the N encoded shards, finalize+decode of the shard.  Returns GB/s per call by the
+    algorithmic bytes of each."""
+    N, L, k = cfg.workers, cfg.shard_len(), cfg.block_log2
+    es = 4 if cfg.dtype == "f32" else 2
+    bf = cfg.dtype != "f32"
+    ns = len(sets)
+    enc = torch.empty_like(sets[0][0])
+    total = torch.empty(L, dtype=torch.float32, device=enc.device)
+    cnt = torch.empty(L, dtype=torch.uint8, device=enc.device)
+    out = torch.empty(L, dtype=enc.dtype, device=enc.device)
+
+    def run(fn, nbytes):
+        for j in range(2):
+            fn(j)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for j in range(iters):
+            fn(j)
+        e1.record()
+        torch.cuda.synchronize()
+        return nbytes / (e0.elapsed_time(e1) * 1e-3 / iters) / 1e9
+
+    if bf:
+        f_enc = lambda j: b.or_rht_encode_bf16(sets[j % ns][0].view(-1), N * L, k, cfg.seed, 0, enc.view(-1))
+        f_red = lambda j: b.or_masked_reduce_bf16(sets[j % ns][0], sets[j % ns][1], N, L, total, cnt)
+        f_dec = lambda j: b.or_finalize_decode_bf16(total, cnt, L, k, cfg.seed, 0, out)
+    else:
+        f_enc = lambda j: b.or_rht_encode(sets[j % ns][0].view(-1), N * L, k, cfg.seed, enc.view(-1))
+        f_red = lambda j: b.or_masked_reduce(sets[j % ns][0], sets[j % ns][1], N, L, total, cnt)
+        f_dec = lambda j: b.or_finalize_decode(total, cnt, L, k, cfg.seed, 0, out)
+    return {"encode_full_gradient_GB_per_s": run(f_enc, 2 * N * L * es),
+            "masked_reduce_GB_per_s": run(f_red, N * L * es + N * L // 8 + 5 * L),
+            "finalize_decode_shard_GB_per_s": run(f_dec, L * (5 + es))}
+
+
 def cpu_baseline(wl, b, cfg, sets, target_seconds=12.0):
     """The oracle, single-threaded on this host, on the first blocks of the same workload; also
     checks the GPU result of those blocks against it."""
@@ -229,6 +267,7 @@ def main():
                      "kernel": "k_fused", "avg_launch_us": kern * 1e6,
                      "kernel_only_us_dispatch_events": kernel_only_seconds(b, cfg, L, sets) * 1e6},
     }
+    result["three_call_path"] = time_three_calls(wl, b, cfg, sets)
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(wl, b, cfg, sets)
     del sets
@@ -271,10 +310,13 @@ def main():
                 else:
                     ps, kn, by, ns, st = time_fused(wl, b, c, device, steps, 2)
                     by_step, ent, note = by, c.workers * c.shard_len(), "one launch per step"
-                extra.append({"workload": name, "GB_per_s": by_step / ps / 1e9, "entries_per_s": ent / ps,
-                              "ms_per_step": ps * 1e3, "avg_launch_us": kn * 1e6,
-                              "launch_GB_per_s": by / kn / 1e9, "frac_hbm_peak": by / kn / 1e9 / HBM_PEAK_GBPS,
-                              "input_sets_rotated": ns, "note": note})
+                row = {"workload": name, "GB_per_s": by_step / ps / 1e9, "entries_per_s": ent / ps,
+                       "ms_per_step": ps * 1e3, "avg_launch_us": kn * 1e6,
+                       "launch_GB_per_s": by / kn / 1e9, "frac_hbm_peak": by / kn / 1e9 / HBM_PEAK_GBPS,
+                       "input_sets_rotated": ns, "note": note}
+                if not c.bucket_entries:
+                    row["three_call_path"] = time_three_calls(wl, b, c, st, iters=5)
+                extra.append(row)
                 del st
                 torch.cuda.empty_cache()
             except Exception as exc:  # an extra workload must not take the headline down with it
