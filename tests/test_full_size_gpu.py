@@ -150,3 +150,66 @@ def test_llama_8b_sized(b, orc):
     cfg = wl.CONFIGS["llama_8b"]
     assert cfg.shard_len() == 1_003_814_912 and cfg.entries > 2 ** 32
     _run_config(b, orc, cfg, shard=7, nsamples=3)     # last shard: base index beyond 2^32, holds the pad
+
+
+def test_llama_8b_full_gradient_encode_and_decode(b, orc):
+    """What a real node does around the exchange: encode its whole 8.03e9-entry bf16 gradient (index
+    range beyond 2^32, ragged last block), later decode the whole aggregated bucket."""
+    from paper_2310_06993_amd import workloads as wl
+    cfg = wl.CONFIGS["llama_8b"]
+    P, k, B = cfg.entries, cfg.block_log2, cfg.block
+    n_pad = b.or_padded_len(P, k)
+    assert P > 2 ** 32 and n_pad - P == 61440 and n_pad % B == 0
+    x = torch.empty(P, dtype=torch.bfloat16, device=dev())
+    g = torch.Generator(device=dev()).manual_seed(55)
+    step = 1 << 28
+    for s0 in range(0, P, step):
+        s1 = min(P, s0 + step)
+        x[s0:s1] = (torch.randn(s1 - s0, device=dev(), generator=g) * 1e-4).to(torch.bfloat16)
+    enc = torch.empty(n_pad, dtype=torch.bfloat16, device=dev())
+    b.or_rht_encode_bf16(x, P, k, cfg.seed, 0, enc)
+    torch.cuda.synchronize()
+    nblocks = n_pad // B
+    picks = [0, 1, (1 << 32) // B - 1, (1 << 32) // B, nblocks // 2 + 3, nblocks - 2, nblocks - 1]
+    for blk in picks:
+        lo, hi = blk * B, min(P, (blk + 1) * B)
+        want = orc.rht_encode(to_np(x[lo:hi]), k, cfg.seed, lo)
+        assert rel_l2(to_np(enc[lo:lo + B]), want) <= TOL["bf16"], blk
+        assert (to_np(enc[lo:lo + B]) != want).mean() < 0.02, blk
+    # decode of the (here: loss-free, single-worker) aggregated bucket gives the gradient back
+    agg = torch.empty(n_pad, dtype=torch.float32, device=dev())
+    for s0 in range(0, n_pad, step):
+        agg[s0:s0 + step] = enc[s0:s0 + step].float()
+    del enc
+    out = torch.empty(P, dtype=torch.bfloat16, device=dev())
+    b.or_rht_decode_bf16(agg, P, k, cfg.seed, 0, out)
+    torch.cuda.synchronize()
+    for blk in picks:
+        lo, hi = blk * B, min(P, (blk + 1) * B)
+        want = orc.rht_decode(to_np(agg[lo:lo + B]), hi - lo, k, cfg.seed, lo, out_dtype=np.uint16)
+        assert rel_l2(to_np(out[lo:hi]), want) <= TOL["bf16"], blk
+        assert rel_l2(to_np(out[lo:hi]), to_np(x[lo:hi])) <= TOL["bf16"], blk
+
+
+def test_bert_large_full_gradient_three_calls(b, orc):
+    """Encode the whole fp32 gradient of one worker (all N shards), then aggregate and decode every
+    shard with encoded inputs, as the separate calls would be used around a real exchange."""
+    from paper_2310_06993_amd import workloads as wl
+    cfg = wl.CONFIGS["bert_large"]
+    N, L, k, B = cfg.workers, cfg.shard_len(), cfg.block_log2, cfg.block
+    P, n_pad = cfg.entries, cfg.padded_entries()
+    assert b.or_padded_len(P, k) <= n_pad
+    x = torch.zeros(n_pad, device=dev())
+    x[:P] = torch.randn(P, device=dev(), generator=torch.Generator(device=dev()).manual_seed(5)) * 1e-3
+    enc = torch.empty(n_pad, device=dev())
+    b.or_rht_encode(x, n_pad, k, cfg.seed, enc)
+    # shard r of the bucket is entries [r L, (r+1) L): check a block in the first, a middle and the last shard
+    for r, blk in ((0, 0), (3, 17), (N - 1, L // B - 1)):
+        lo = r * L + blk * B
+        want = orc.rht_encode(to_np(x[lo:lo + B]), k, cfg.seed, lo)
+        assert rel_l2(to_np(enc[lo:lo + B]), want) <= TOL["f32"]
+    # a single worker's bucket decodes back to itself through finalize+decode with count 1
+    cnt = torch.ones(n_pad, dtype=torch.uint8, device=dev())
+    back = torch.empty(P, device=dev())
+    b.or_finalize_decode(enc, cnt, P, k, cfg.seed, 0, back)
+    assert float((back.double() - x[:P].double()).norm() / x[:P].double().norm()) <= TOL["f32"]
