@@ -322,38 +322,43 @@ __device__ __forceinline__ void fused_tile(const PathArgs& a, u64 unit) {
   const float sigma = lane_sigma(lane, kt < 6 ? kt : 6);
   // a power-of-two scale commutes with rounding to the wire type; any other scale is applied first
   const bool scale_first = sizeof(In) == 2 && (a.k & 1);
-  u64 sg[R];
-  uint32_t sw[Geo<K>::PARTS] = {};
-  if constexpr (Geo<K>::PARTS == 1) sign_masks(a.seed, a.base + e0 + (u64)wave * Geo<K>::WAVE_ENTRIES, sg);
-  else part_sign_words<K>(unit, a.seed, a.base, wave, sw);
   float acc[R], va[R];
   uint32_t cnt[R / 4];
   int full = 0, flip = 0;
+  const int moff = mask_word_offset<K>(wave, lane);
+  const u64 mrow = L >> 5;
+  uint32_t ma;
+  u64 sg[R];
+  uint32_t sw[Geo<K>::PARTS] = {};
+  if constexpr (Geo<K>::PARTS == 1) {
+    // the first worker's tile is requested before the signs are computed, so Philox runs under its latency
+    load_tile<K, false, FULL>(grads, e0, L, wave, lane, va);
+    ma = load_mask_words<K, FULL>(a.masks, e0, L, moff);
+    sign_masks(a.seed, a.base + e0 + (u64)wave * Geo<K>::WAVE_ENTRIES, sg);
+  } else {
+    part_sign_words<K>(unit, a.seed, a.base, wave, sw);
+    load_raw_tile<K, FULL>(grads, L, unit, wave, lane, va, sw);
+    ma = load_mask_words<K, FULL>(a.masks, e0, L, moff);
+  }
 #pragma unroll
   for (int r = 0; r < R; ++r) acc[r] = 0.0f;
 #pragma unroll
   for (int r = 0; r < R / 4; ++r) cnt[r] = 0;
 
-  const int moff = mask_word_offset<K>(wave, lane);
-  const u64 mrow = L >> 5;
-  uint32_t ma;
-
-  auto step = [&](float (&v)[R], uint32_t m) {
-    if constexpr (Geo<K>::PARTS == 1) apply_signs(v, sg);
-    transform<K, true, NB != 2>(v, xbuf[NB == 2 ? flip : 0], wave, lane, kt);
+  for (int i = 0; i < a.N; ++i) {
+    if constexpr (Geo<K>::PARTS == 1) apply_signs(va, sg);
+    transform<K, true, NB != 2>(va, xbuf[NB == 2 ? flip : 0], wave, lane, kt);
     flip ^= 1;
     if (sizeof(In) == 2) {
       const float pre = scale_first ? a.scale : 1.0f;
 #pragma unroll
-      for (int r = 0; r < R; ++r) v[r] = round_to<In>(v[r] * pre);
+      for (int r = 0; r < R; ++r) va[r] = round_to<In>(va[r] * pre);
     }
-    masked_accumulate(v, m, acc, cnt, full);
-  };
-
-  for (int i = 0; i < a.N; ++i) {
-    load_raw_tile<K, FULL>(grads + (u64)i * L, L, unit, wave, lane, va, sw);
-    ma = load_mask_words<K, FULL>(a.masks + (u64)i * mrow, e0, L, moff);
-    step(va, ma);
+    masked_accumulate(va, ma, acc, cnt, full);
+    if (i + 1 < a.N) {
+      load_raw_tile<K, FULL>(grads + (u64)(i + 1) * L, L, unit, wave, lane, va, sw);
+      ma = load_mask_words<K, FULL>(a.masks + (u64)(i + 1) * mrow, e0, L, moff);
+    }
   }
   __builtin_amdgcn_sched_barrier(0);
   store_counts<K, FULL>(a.count_out, e0, L, wave, lane, cnt, full);

@@ -36,11 +36,16 @@ namespace ordev {
 
 typedef unsigned long long u64;
 
+// Entries per lane: 32 for blocks of 2^13 and 2^14 entries (a 64 KB tile then needs 8 wavefronts, so two
+// workgroups fit on a CU), 16 otherwise.  Both choices were measured on MI355X against the alternative.
 #ifndef OR_RL_BIG
-#define OR_RL_BIG 5   // log2(entries per lane) for blocks of 2^OR_RL_FROM entries and above
+#define OR_RL_BIG 5
 #endif
 #ifndef OR_RL_FROM
 #define OR_RL_FROM 13
+#endif
+#ifndef OR_RL_TO
+#define OR_RL_TO 14
 #endif
 
 // Geometry for a block of 2^K entries.  KT bits are transformed inside a tile; for
@@ -52,9 +57,6 @@ struct Geo {
   static constexpr int KT = (K == 0) ? 10 : (K > 14 ? 14 : K);
   static constexpr int TL = KT;
   static constexpr int T = 1 << TL;
-#ifndef OR_RL_TO
-#define OR_RL_TO 14
-#endif
   static constexpr int RL = (K != 0 && K >= OR_RL_FROM && K <= OR_RL_TO) ? OR_RL_BIG : 4;
   static constexpr int R = 1 << RL;
   static constexpr int Q = TL - 6 - RL;          // wave bits
@@ -202,14 +204,11 @@ __device__ __forceinline__ void lane_stage(float (&v)[NR], int lane) {
     if constexpr (NR == 32) OR_FMAC_DPP16(v, 16, s, "row_ror:8");
   } else {
     const int a32 = (lane ^ 32) << 2;
-#ifndef OR_XLANE_CHUNK
-#define OR_XLANE_CHUNK 8
-#endif
-    // in chunks, so that at most OR_XLANE_CHUNK partner values are live at a time
+    // in chunks of 8 registers, so that at most 8 partner values are live at a time
 #pragma unroll
-    for (int o = 0; o < NR; o += OR_XLANE_CHUNK) {
+    for (int o = 0; o < NR; o += 8) {
 #pragma unroll
-      for (int r = o; r < o + OR_XLANE_CHUNK; ++r) {
+      for (int r = o; r < o + 8; ++r) {
         int i = __builtin_bit_cast(int, v[r]);
         int p = BIT == 4 ? __builtin_amdgcn_ds_swizzle(i, 0x401F) : __builtin_amdgcn_ds_bpermute(a32, i);
         v[r] = __builtin_fmaf(__builtin_bit_cast(float, p), s, v[r]);
