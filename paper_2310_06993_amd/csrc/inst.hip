@@ -65,8 +65,17 @@ OR_LAUNCHER(fus_bf16, (k_fused<K, bf16_t, true>))
 OR_BATCH_LAUNCHER(fusb_f32, (k_fused_batched<K, float>))
 OR_BATCH_LAUNCHER(fusb_bf16, (k_fused_batched<K, bf16_t>))
 #else
-OR_LAUNCHER(fus_f32, (k_fused<K, float, false>))
-OR_LAUNCHER(fus_bf16, (k_fused<K, bf16_t, false>))
+// one workgroup per pair of output tiles; `units` = output tiles of the shard
+#define OR_PAIR_LAUNCHER(name, kernel)                                                       \
+  hipError_t name(const PathArgs& a, unsigned long long units, hipStream_t s, int pos) {    \
+    if (units == 0) return hipSuccess;                                                       \
+    const unsigned long long blocks = units >> G::HB, per = G::PARTS / 2;                    \
+    unsigned long long grid = per == 1 ? blocks : (blocks + 7) / 8 * 8 * per;                \
+    if (grid > 0x7FFFFFFFull) return hipErrorInvalidValue;                                   \
+    return launch_kernel(kernel, dim3((unsigned)grid), dim3(G::THREADS), s, pos, a);         \
+  }
+OR_PAIR_LAUNCHER(fus_f32, (k_fused_pairs<K, float>))
+OR_PAIR_LAUNCHER(fus_bf16, (k_fused_pairs<K, bf16_t>))
 #endif
 }  // namespace
 

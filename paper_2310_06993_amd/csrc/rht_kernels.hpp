@@ -386,6 +386,109 @@ void k_fused(PathArgs a) {
   fused_tile<K, In, DECODE>(a, unit);
 }
 
+// ---------------------------------------------------------------------------------------------------
+// The fused path for blocks of 2^15 / 2^16 entries (PARTS = 2 / 4 tiles per block).  A workgroup produces
+// TWO output tiles of its block, p_lo = h and p_hi = h + PARTS/2, from one reading of the block's input
+// tiles: with u_q the signed input tiles and H_{2P} = [[H_P, H_P], [H_P, -H_P]],
+//     A = sum_{q <  P/2} H[h][q] u_q,   C = sum_{q >= P/2} H[h][q - P/2] u_q,   p_lo = A + C,  p_hi = A - C,
+// so the +-1 combination costs half the sign flips and adds per output of the one-tile-per-workgroup
+// form, and the inputs are read PARTS/2 times instead of PARTS times.  It stops at the fp32 mean
+// (layout B) in `mean_out`; k_decode finishes.
+template <int K, class In>
+__global__ __launch_bounds__(Geo<K>::THREADS) void k_fused_pairs(PathArgs a) {
+  constexpr int T = Geo<K>::T, R = Geo<K>::R, HB = Geo<K>::HB, PARTS = Geo<K>::PARTS, HP = PARTS / 2;
+  static_assert(PARTS == 2 || PARTS == 4, "two or four tiles per block");
+  __shared__ float xbuf[T];
+  const int wave = wave_id(), lane = lane_id(), kt = Geo<K>::KT;
+  const u64 L = a.n_pad, nblocks = L >> K;
+  // workgroup -> (block, h); the HP workgroups of a block sit on one XCD, next to each other
+  u64 blk;
+  int h;
+  if constexpr (HP == 1) {
+    blk = blockIdx.x;
+    h = 0;
+  } else {
+    const u64 x = blockIdx.x, slot = x >> 3;
+    h = (int)(slot & (HP - 1));
+    blk = ((slot / HP) << 3) + (x & 7);
+  }
+  if (blk >= nblocks) return;
+  const u64 t0 = blk << HB;                      // first tile of the block
+  const u64 e_lo = (t0 + h) * T, e_hi = (t0 + h + HP) * T;
+  const In* grads = (const In*)a.in;
+  const float sigma = lane_sigma(lane, 6);
+  const bool scale_first = sizeof(In) == 2 && (a.k & 1);
+  const int moff = mask_word_offset<K>(wave, lane);
+  const u64 mrow = L >> 5;
+
+  uint32_t sw[PARTS];
+#pragma unroll
+  for (int q = 0; q < PARTS; ++q)
+    sw[q] = sign_words<R>(a.seed, a.base + (t0 + q) * T + (u64)wave * Geo<K>::WAVE_ENTRIES);
+
+  float acc_lo[R], acc_hi[R];
+  uint32_t cnt_lo[R / 4], cnt_hi[R / 4];
+  int full_lo = 0, full_hi = 0;
+#pragma unroll
+  for (int r = 0; r < R; ++r) acc_lo[r] = acc_hi[r] = 0.0f;
+#pragma unroll
+  for (int r = 0; r < R / 4; ++r) cnt_lo[r] = cnt_hi[r] = 0;
+
+  // dst (+)= coef * (signed t)
+  auto add_signed = [&](float (&dst)[R], const float (&t)[R], uint32_t words, float coef, bool first) {
+    uint32_t w = words;
+    asm volatile("" : "+v"(w));   // the lane masks of a tile are formed where the tile is used, not hoisted
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const float ts = in_mask(mask_of_reg(w, r)) ? -t[r] : t[r];
+      dst[r] = first ? coef * ts : __builtin_fmaf(coef, ts, dst[r]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto finish_tile = [&](float (&v)[R], uint32_t m, float (&acc)[R], uint32_t (&cnt)[R / 4], int& full) {
+    transform<K, true, true>(v, xbuf, wave, lane, kt);
+    if (sizeof(In) == 2) {
+      const float pre = scale_first ? a.scale : 1.0f;
+#pragma unroll
+      for (int r = 0; r < R; ++r) v[r] = round_to<In>(v[r] * pre);
+    }
+    masked_accumulate(v, m, acc, cnt, full);
+  };
+
+  for (int i = 0; i < a.N; ++i) {
+    const In* x = grads + (u64)i * L;
+    float A[R], C[R], t[R], w[R];
+    // up to three tiles in flight: u_0 -> A, u_1 -> t (four-tile blocks), u_HP -> C
+    load_tile<K, false, true>(x, t0 * T, L, wave, lane, A);
+    if constexpr (HP == 2) load_tile<K, false, true>(x, (t0 + 1) * T, L, wave, lane, t);
+    load_tile<K, false, true>(x, (t0 + HP) * T, L, wave, lane, C);
+    const uint32_t m_lo = load_mask_words<K, true>(a.masks + (u64)i * mrow, e_lo, L, moff);
+    const uint32_t m_hi = load_mask_words<K, true>(a.masks + (u64)i * mrow, e_hi, L, moff);
+    add_signed(A, A, sw[0], 1.0f, true);
+    if constexpr (HP == 2) {
+      add_signed(A, t, sw[1], part_coef(h, 1), false);
+      load_tile<K, false, true>(x, (t0 + HP + 1) * T, L, wave, lane, t);
+    }
+    add_signed(C, C, sw[HP], 1.0f, true);
+    if constexpr (HP == 2) add_signed(C, t, sw[HP + 1], part_coef(h, 1), false);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      w[r] = A[r] + C[r];
+      C[r] = A[r] - C[r];
+    }
+    finish_tile(w, m_lo, acc_lo, cnt_lo, full_lo);
+    finish_tile(C, m_hi, acc_hi, cnt_hi, full_hi);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  const float post = sigma * (scale_first ? 1.0f : a.scale);
+  store_counts<K, true>(a.count_out, e_lo, L, wave, lane, cnt_lo, full_lo);
+  finalize_mean(acc_lo, cnt_lo, full_lo, post);
+  store_tile<K, true, true>(a.mean_out, e_lo, L, wave, lane, acc_lo);
+  store_counts<K, true>(a.count_out, e_hi, L, wave, lane, cnt_hi, full_hi);
+  finalize_mean(acc_hi, cnt_hi, full_hi, post);
+  store_tile<K, true, true>(a.mean_out, e_hi, L, wave, lane, acc_hi);
+}
+
 // Several buckets of one launch shape class (same N, block size and type) in ONE launch: small buckets
 // (a 25 MiB DDP bucket is only ~100 tiles per shard) cannot fill 256 CUs on their own.  Descriptors ride
 // in the kernel arguments; workgroup x serves tile x - tile_start[j] of bucket j.
