@@ -204,6 +204,18 @@ def cpu_baseline(wl, b, cfg, sets, target_seconds=12.0):
     }
 
 
+def profiled_traffic(workload):
+    """HBM bytes per launch of the dominant kernel as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    (scaled by a known-size copy); taken from the committed summary under profiles/, null if there is none."""
+    import re
+    path = os.path.join(ROOT, "profiles", "k_fused_%s.md" % workload)
+    try:
+        m = re.search(r"traffic = (\d+) bytes per launch", open(path).read())
+        return int(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -263,7 +275,7 @@ def main():
                    "entry_point": "or_fused_path" if cfg.dtype == "f32" else "or_fused_path_bf16",
                    "input_sets_rotated": nsets, "bytes_per_step": nbytes},
         "roofline": {"bound": "hbm", "achieved": nbytes / kern / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": nbytes / kern / 1e9 / HBM_PEAK_GBPS, "traffic": None,
+                     "frac": nbytes / kern / 1e9 / HBM_PEAK_GBPS, "traffic": profiled_traffic(cfg.name),
                      "kernel": "k_fused", "avg_launch_us": kern * 1e6,
                      "kernel_only_us_dispatch_events": kernel_only_seconds(b, cfg, L, sets) * 1e6},
     }

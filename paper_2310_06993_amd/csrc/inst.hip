@@ -60,8 +60,8 @@ OR_SPLIT_LAUNCHER(mdec_bf16, (k_decode<K, bf16_t, false, true, true>), (k_decode
 #if OR_K <= 14
 OR_LAUNCHER(rdec_f32, (k_reduce_decode<K, float, float>))
 OR_LAUNCHER(rdec_bf16, (k_reduce_decode<K, bf16_t, bf16_t>))
-OR_LAUNCHER(fus_f32, (k_fused<K, float, true>))
-OR_LAUNCHER(fus_bf16, (k_fused<K, bf16_t, true>))
+OR_LAUNCHER(fus_f32, (k_fused<K, float>))
+OR_LAUNCHER(fus_bf16, (k_fused<K, bf16_t>))
 OR_BATCH_LAUNCHER(fusb_f32, (k_fused_batched<K, float>))
 OR_BATCH_LAUNCHER(fusb_bf16, (k_fused_batched<K, bf16_t>))
 #else

@@ -305,16 +305,16 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_reduce_decode(PathArgs a) {
 // The whole path for one shard held by one node: the raw slices of N workers are encoded, the
 // encoded entries that arrived are summed and counted, the mean is decoded.  The encoded value is
 // rounded to the wire type (identity for fp32) before it is summed, so the result is the one the
-// three separate calls give.  DECODE = false (blocks above 2^14) stops at the fp32 mean.
+// three separate calls give.  Blocks of up to 2^14 entries (one tile per block).
 //
 // Per worker: sign flip (layout A), transform to layout B, round, add under the received mask.
 // No register prefetch of the next worker's tile: measured on MI355X, keeping the kernel small enough
 // for several independent workgroups per CU hides the load latency better than a second tile buffer.
-template <int K, class In, bool DECODE>
+template <int K, class In>
 __device__ __forceinline__ void fused_tile(const PathArgs& a, u64 unit) {
   constexpr int T = Geo<K>::T, NB = kXbufs<K>, R = Geo<K>::R;
   constexpr bool FULL = kShardTilesFull<K>;
-  static_assert(DECODE == (Geo<K>::PARTS == 1), "decode in the same kernel only when a block is one tile");
+  static_assert(Geo<K>::PARTS == 1, "larger blocks use k_fused_pairs");
   __shared__ float xbuf[NB ? NB : 1][NB ? T : 1];
   const int wave = wave_id(), lane = lane_id(), kt = tile_bits<K>(a.k);
   const u64 L = a.n_pad, e0 = unit * T;
@@ -327,26 +327,18 @@ __device__ __forceinline__ void fused_tile(const PathArgs& a, u64 unit) {
   int full = 0, flip = 0;
   const int moff = mask_word_offset<K>(wave, lane);
   const u64 mrow = L >> 5;
-  uint32_t ma;
+  // the first worker's tile is requested before the signs are computed, so Philox runs under its latency
+  load_tile<K, false, FULL>(grads, e0, L, wave, lane, va);
+  uint32_t ma = load_mask_words<K, FULL>(a.masks, e0, L, moff);
   u64 sg[R];
-  uint32_t sw[Geo<K>::PARTS] = {};
-  if constexpr (Geo<K>::PARTS == 1) {
-    // the first worker's tile is requested before the signs are computed, so Philox runs under its latency
-    load_tile<K, false, FULL>(grads, e0, L, wave, lane, va);
-    ma = load_mask_words<K, FULL>(a.masks, e0, L, moff);
-    sign_masks(a.seed, a.base + e0 + (u64)wave * Geo<K>::WAVE_ENTRIES, sg);
-  } else {
-    part_sign_words<K>(unit, a.seed, a.base, wave, sw);
-    load_raw_tile<K, FULL>(grads, L, unit, wave, lane, va, sw);
-    ma = load_mask_words<K, FULL>(a.masks, e0, L, moff);
-  }
+  sign_masks(a.seed, a.base + e0 + (u64)wave * Geo<K>::WAVE_ENTRIES, sg);
 #pragma unroll
   for (int r = 0; r < R; ++r) acc[r] = 0.0f;
 #pragma unroll
   for (int r = 0; r < R / 4; ++r) cnt[r] = 0;
 
   for (int i = 0; i < a.N; ++i) {
-    if constexpr (Geo<K>::PARTS == 1) apply_signs(va, sg);
+    apply_signs(va, sg);
     transform<K, true, NB != 2>(va, xbuf[NB == 2 ? flip : 0], wave, lane, kt);
     flip ^= 1;
     if (sizeof(In) == 2) {
@@ -356,7 +348,7 @@ __device__ __forceinline__ void fused_tile(const PathArgs& a, u64 unit) {
     }
     masked_accumulate(va, ma, acc, cnt, full);
     if (i + 1 < a.N) {
-      load_raw_tile<K, FULL>(grads + (u64)(i + 1) * L, L, unit, wave, lane, va, sw);
+      load_tile<K, false, FULL>(grads + (u64)(i + 1) * L, e0, L, wave, lane, va);
       ma = load_mask_words<K, FULL>(a.masks + (u64)(i + 1) * mrow, e0, L, moff);
     }
   }
@@ -364,26 +356,19 @@ __device__ __forceinline__ void fused_tile(const PathArgs& a, u64 unit) {
   store_counts<K, FULL>(a.count_out, e0, L, wave, lane, cnt, full);
   finalize_mean(acc, cnt, full, sigma * (scale_first ? 1.0f : a.scale));
   __builtin_amdgcn_sched_barrier(0);
-  if constexpr (DECODE) {
-    transform<K, false, NB != 2>(acc, xbuf[NB == 2 ? flip : 0], wave, lane, kt);
-    __builtin_amdgcn_sched_barrier(0);
-    const float c = a.scale * sigma;
+  transform<K, false, NB != 2>(acc, xbuf[NB == 2 ? flip : 0], wave, lane, kt);
+  __builtin_amdgcn_sched_barrier(0);
+  const float c = a.scale * sigma;
 #pragma unroll
-    for (int r = 0; r < R; ++r) acc[r] *= c;
-    apply_signs(acc, sg);
-    store_tile<K, false, FULL, true>((In*)a.out, e0, L, wave, lane, acc);
-  } else {
-    store_tile<K, true, FULL>(a.mean_out, e0, L, wave, lane, acc);
-  }
+  for (int r = 0; r < R; ++r) acc[r] *= c;
+  apply_signs(acc, sg);
+  store_tile<K, false, FULL, true>((In*)a.out, e0, L, wave, lane, acc);
 }
 
-template <int K, class In, bool DECODE>
+template <int K, class In>
 __global__ __launch_bounds__(Geo<K>::THREADS) __attribute__((amdgpu_waves_per_eu(Geo<K>::R == 32 ? 4 : 1)))
 void k_fused(PathArgs a) {
-  bool none;
-  const u64 unit = unit_of_workgroup<K>(a.unit0, a.unit_end, none);
-  if (none) return;
-  fused_tile<K, In, DECODE>(a, unit);
+  fused_tile<K, In>(a, blockIdx.x);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -517,7 +502,7 @@ void k_fused_batched(BatchArgs ba) {
   a.in = ba.b[j].in; a.masks = ba.b[j].masks; a.out = ba.b[j].out; a.count_out = ba.b[j].count_out;
   a.n = a.n_pad = ba.b[j].shard_len; a.seed = ba.b[j].seed; a.base = ba.b[j].base;
   a.N = ba.N; a.k = ba.k; a.scale = ba.scale;
-  fused_tile<K, In, true>(a, x - ba.tile_start[j]);
+  fused_tile<K, In>(a, x - ba.tile_start[j]);
 }
 
 }  // namespace ordev
