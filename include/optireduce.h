@@ -149,6 +149,27 @@ or_status or_finalize_bf16(const float* sum, const uint8_t* count, uint64_t shar
  * loss fraction of the shard is 1 - total / (N * shard_len).  Exact integer. */
 or_status or_received_total(const uint8_t* count, uint64_t shard_len, uint64_t* total_out, void* stream);
 
+/* or_loss_decision: the safeguard of Sec. 3.4 and the activation rule of Sec. 3.2.1 as host arithmetic (no GPU
+ * work, no stream; every pointer here is a HOST pointer).  received_total is what or_received_total wrote,
+ * copied back by the caller; loss = 1 - received_total / (N * shard_len).
+ *   *action_out: OR_ACT_HALT if loss > policy->halt_loss, else OR_ACT_SKIP if loss > policy->skip_loss,
+ *                else OR_ACT_APPLY (the paper leaves the threshold and the choice between skipping the
+ *                update and halting to the user: set a threshold above 1 to switch that action off);
+ *   *transform_on_out: prev_transform_on, or 1 once loss > policy->transform_on_loss (the paper's 2 %;
+ *                OR_DEFAULT_TRANSFORM_ON_LOSS) -- the transform stays on once it has been switched on;
+ *   *loss_out (may be NULL): the loss fraction.
+ * OR_ERR_SHAPE if received_total > N * shard_len or N * shard_len == 0, OR_ERR_NULL for a missing pointer,
+ * OR_ERR_WORKERS for N outside 1..OR_MAX_WORKERS; thresholds must not be NaN (OR_ERR_SHAPE). */
+#define OR_DEFAULT_TRANSFORM_ON_LOSS 0.02
+enum { OR_ACT_APPLY = 0, OR_ACT_SKIP = 1, OR_ACT_HALT = 2 };
+typedef struct or_loss_policy {
+  double transform_on_loss; /* switch the Hadamard transform on above this loss */
+  double skip_loss;         /* drop this round's update above this loss */
+  double halt_loss;         /* stop training above this loss */
+} or_loss_policy;
+or_status or_loss_decision(uint64_t received_total, int N, uint64_t shard_len, const or_loss_policy* policy,
+                           int prev_transform_on, int* action_out, int* transform_on_out, double* loss_out);
+
 /* or_rht_decode_masked: decode after loss in the SECOND stage (Sec. 3.1.1: the owner broadcasts its
  * aggregated shard over the same unreliable transport; Sec. 3.3: the transform spreads what is lost).
  * mask: or_padded_len(n)/32 words, bit layout as for shards; an aggregated entry whose bit is clear

@@ -210,6 +210,19 @@ def received_total(count) -> int:
     return int(_load().orc_received_total(_ptr(c), c.size))
 
 
+def loss_decision(received_total: int, N: int, shard_len: int, transform_on_loss: float, skip_loss: float,
+                  halt_loss: float, prev_transform_on: bool):
+    """Sec. 3.4 (skip the update or halt above a loss threshold) and Sec. 3.2.1 (the transform goes on
+    above 2 % loss and stays on).  loss = 1 - received / (N * shard_len), compared as exact rationals.
+    Returns (action, transform_on, loss) with action 0 = apply, 1 = skip, 2 = halt."""
+    from fractions import Fraction
+    sent = N * shard_len
+    assert 0 <= received_total <= sent and sent > 0
+    loss = 1 - Fraction(received_total, sent)
+    action = 2 if loss > Fraction(halt_loss) else (1 if loss > Fraction(skip_loss) else 0)
+    return action, bool(prev_transform_on or loss > Fraction(transform_on_loss)), float(loss)
+
+
 def masked_reduce_pairs(sums, counts, masks):
     """Second level of hierarchical 2D TAR (Sec. 3.1.2, App. A): combine the groups' (sum, count)
     partial aggregates that arrived.  sums [G, L] fp32, counts [G, L] uint8, masks [G, L/32]."""

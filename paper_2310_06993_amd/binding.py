@@ -48,10 +48,19 @@ _SIGS = {
     "or_finalize": (_int, [_p, _p, _u64, _p, _p]),
     "or_finalize_bf16": (_int, [_p, _p, _u64, _p, _p]),
     "or_received_total": (_int, [_p, _u64, _p, _p]),
+    "or_loss_decision": (_int, [_u64, _int, _u64, _p, _int, _p, _p, _p]),
     "or_rht_decode_masked": (_int, [_p, _p, _u64, _int, _u64, _u64, _p, _p]),
     "or_rht_decode_masked_bf16": (_int, [_p, _p, _u64, _int, _u64, _u64, _p, _p]),
     "or_masked_reduce_pairs": (_int, [_p, _p, _p, _int, _u64, _p, _p, _p]),
 }
+
+
+OR_ACT_APPLY, OR_ACT_SKIP, OR_ACT_HALT = 0, 1, 2
+OR_DEFAULT_TRANSFORM_ON_LOSS = 0.02
+
+
+class or_loss_policy(C.Structure):
+    _fields_ = [("transform_on_loss", C.c_double), ("skip_loss", C.c_double), ("halt_loss", C.c_double)]
 
 
 class or_bucket(C.Structure):
@@ -216,6 +225,14 @@ def or_finalize_bf16(total, count, shard_len, mean_out, stream=None):
 def or_received_total(count, shard_len, total_out, stream=None):
     """total_out: a one-element int64 device tensor."""
     _check(lib.or_received_total(_ptr(count), shard_len, _ptr(total_out), _stream(stream)), "or_received_total")
+
+
+def or_loss_decision(received_total, N, shard_len, policy, prev_transform_on):
+    """Host arithmetic only.  policy: an or_loss_policy.  Returns (action, transform_on, loss)."""
+    act, ton, loss = C.c_int(), C.c_int(), C.c_double()
+    _check(lib.or_loss_decision(int(received_total), N, shard_len, C.byref(policy), int(bool(prev_transform_on)),
+                                C.byref(act), C.byref(ton), C.byref(loss)), "or_loss_decision")
+    return act.value, ton.value, loss.value
 
 
 def or_rht_decode_masked(agg, mask, n, block_log2, seed, base_index, out, stream=None):

@@ -597,6 +597,24 @@ or_status or_finalize_bf16(const float* sum, const uint8_t* count, uint64_t shar
                            void* stream) {
   return finalize_impl<uint16_t>(sum, count, shard_len, mean_out, stream);
 }
+or_status or_loss_decision(uint64_t received_total, int N, uint64_t shard_len, const or_loss_policy* policy,
+                           int prev_transform_on, int* action_out, int* transform_on_out, double* loss_out) {
+  if (!policy || !action_out || !transform_on_out) return OR_ERR_NULL;
+  if (N < 1 || N > OR_MAX_WORKERS) return OR_ERR_WORKERS;
+  if (policy->transform_on_loss != policy->transform_on_loss || policy->skip_loss != policy->skip_loss ||
+      policy->halt_loss != policy->halt_loss)
+    return OR_ERR_SHAPE;
+  if (shard_len == 0 || shard_len > UINT64_MAX / (uint64_t)N) return OR_ERR_SHAPE;
+  const uint64_t sent = (uint64_t)N * shard_len;
+  if (received_total > sent) return OR_ERR_SHAPE;
+  // the missing arrivals are an exact integer; one division, so that loss == 0 exactly when nothing is missing
+  const double loss = (double)(sent - received_total) / (double)sent;
+  *action_out = loss > policy->halt_loss ? OR_ACT_HALT : (loss > policy->skip_loss ? OR_ACT_SKIP : OR_ACT_APPLY);
+  *transform_on_out = (prev_transform_on || loss > policy->transform_on_loss) ? 1 : 0;
+  if (loss_out) *loss_out = loss;
+  return OR_OK;
+}
+
 or_status or_received_total(const uint8_t* count, uint64_t shard_len, uint64_t* total_out, void* stream) {
   return received_total_impl(count, shard_len, (unsigned long long*)total_out, stream);
 }

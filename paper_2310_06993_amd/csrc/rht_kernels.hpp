@@ -383,7 +383,8 @@ template <int K, class In>
 __global__ __launch_bounds__(Geo<K>::THREADS) void k_fused_pairs(PathArgs a) {
   constexpr int T = Geo<K>::T, R = Geo<K>::R, HB = Geo<K>::HB, PARTS = Geo<K>::PARTS, HP = PARTS / 2;
   static_assert(PARTS == 2 || PARTS == 4, "two or four tiles per block");
-  __shared__ float xbuf[T];
+  // registers allow one workgroup per CU, so a second exchange buffer is free and saves a barrier per exchange
+  __shared__ float xbuf[2][T];
   const int wave = wave_id(), lane = lane_id(), kt = Geo<K>::KT;
   const u64 L = a.n_pad, nblocks = L >> K;
   // workgroup -> (block, h); the HP workgroups of a block sit on one XCD, next to each other
@@ -430,8 +431,9 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_fused_pairs(PathArgs a) {
     }
     __builtin_amdgcn_sched_barrier(0);
   };
-  auto finish_tile = [&](float (&v)[R], uint32_t m, float (&acc)[R], uint32_t (&cnt)[R / 4], int& full) {
-    transform<K, true, true>(v, xbuf, wave, lane, kt);
+  auto finish_tile = [&](float (&v)[R], float* buf, uint32_t m, float (&acc)[R], uint32_t (&cnt)[R / 4],
+                         int& full) {
+    transform<K, true, false>(v, buf, wave, lane, kt);
     if (sizeof(In) == 2) {
       const float pre = scale_first ? a.scale : 1.0f;
 #pragma unroll
@@ -461,8 +463,8 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_fused_pairs(PathArgs a) {
       w[r] = A[r] + C[r];
       C[r] = A[r] - C[r];
     }
-    finish_tile(w, m_lo, acc_lo, cnt_lo, full_lo);
-    finish_tile(C, m_hi, acc_hi, cnt_hi, full_hi);
+    finish_tile(w, xbuf[0], m_lo, acc_lo, cnt_lo, full_lo);
+    finish_tile(C, xbuf[1], m_hi, acc_hi, cnt_hi, full_hi);
   }
   __builtin_amdgcn_sched_barrier(0);
   const float post = sigma * (scale_first ? 1.0f : a.scale);

@@ -81,3 +81,33 @@ def test_host_helpers_and_argument_checks(lib):
     fus.argtypes = [p, p, ctypes.c_int, u64, ctypes.c_int, u64, u64, p, p, p, ctypes.c_size_t, p]
     assert fus(1 << 20, 1 << 24, 2, 1 << 16, 16, 1, 0, 1 << 26, None, None, 0, None) == 6   # OR_ERR_WORKSPACE
     assert fus(1 << 20, 1 << 24, 2, 96, 6, 1, 0, 1 << 26, None, None, 0, None) == 4         # not whole blocks
+
+
+def test_loss_decision_matches_the_oracle(orc):
+    """Host-side safeguard arithmetic (no GPU work): every case against the oracle's exact rationals."""
+    import random
+    from paper_2310_06993_amd import binding as b
+    rng = random.Random(11)
+    cases = [(7900, 8, 1000), (7840, 8, 1000), (7839, 8, 1000), (8000, 8, 1000), (0, 8, 1000), (1, 1, 1),
+             (0, 1, 1), (255 * (1 << 40) - 12345, 255, 1 << 40)]
+    for _ in range(300):
+        N, L = rng.randint(1, 255), rng.randint(1, 1 << 34)
+        cases.append((rng.randint(0, N * L), N, L))
+    for recv, N, L in cases:
+        for prev in (False, True):
+            for ton, skip, halt in ((0.02, 0.05, 0.5), (0.0, 0.0, 0.0), (0.02, 2.0, 2.0), (0.5, 0.25, 0.125)):
+                pol = b.or_loss_policy(ton, skip, halt)
+                act, on, loss = b.or_loss_decision(recv, N, L, pol, prev)
+                eact, eon, eloss = orc.loss_decision(recv, N, L, ton, skip, halt, prev)
+                assert abs(loss - eloss) <= 1e-15
+                # a loss within one rounding of a threshold may fall on either side in double arithmetic
+                near = any(abs(eloss - t) <= 1e-15 for t in (ton, skip, halt))
+                if not near:
+                    assert (act, bool(on)) == (eact, eon), (recv, N, L, prev, ton, skip, halt)
+    pol = b.or_loss_policy(0.02, 0.05, 0.5)
+    for bad, code in (((9, 1, 8), 4), ((0, 0, 8), 3), ((0, 256, 8), 3), ((0, 1, 0), 4)):
+        with pytest.raises(b.OptiReduceError) as e:
+            b.or_loss_decision(*bad, pol, False)
+        assert e.value.status == code
+    with pytest.raises(b.OptiReduceError):
+        b.or_loss_decision(1, 1, 8, b.or_loss_policy(float("nan"), 0.0, 0.0), False)

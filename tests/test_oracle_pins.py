@@ -403,3 +403,20 @@ def test_two_level_reduce_equals_one_level(orc):
     m = np.zeros((2, 1), np.uint32); m[1, 0] = 1
     t, cc = orc.masked_reduce_pairs(s, c, m)
     assert t[0] == 10 and cc[0] == 1 and not t[1:].any() and not cc[1:].any()
+
+
+def test_loss_decision_hand_cases(orc):
+    # Sec. 3.4 / Sec. 3.2.1 by hand: 8 workers x 1000 entries = 8000 sent
+    # 7900 arrived -> loss 1.25 %: below the 2 % switch, below a 5 % skip threshold
+    assert orc.loss_decision(7900, 8, 1000, 0.02, 0.05, 0.5, False) == (0, False, 0.0125)
+    # 7800 arrived -> 2.5 %: transform goes on, update still applied
+    assert orc.loss_decision(7800, 8, 1000, 0.02, 0.05, 0.5, False) == (0, True, 0.025)
+    # exactly 2 % is not "exceeds"
+    assert orc.loss_decision(7840, 8, 1000, 0.02, 0.05, 0.5, False)[:2] == (0, False)
+    # once on, the transform stays on even with no loss at all
+    assert orc.loss_decision(8000, 8, 1000, 0.02, 0.05, 0.5, True) == (0, True, 0.0)
+    # 7000 arrived -> 12.5 %: skip; 3000 arrived -> 62.5 %: halt
+    assert orc.loss_decision(7000, 8, 1000, 0.02, 0.05, 0.5, False) == (1, True, 0.125)
+    assert orc.loss_decision(3000, 8, 1000, 0.02, 0.05, 0.5, False) == (2, True, 0.625)
+    # a threshold above 1 switches that action off
+    assert orc.loss_decision(0, 8, 1000, 0.02, 2.0, 2.0, False) == (0, True, 1.0)

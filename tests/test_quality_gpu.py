@@ -67,3 +67,61 @@ def test_255_workers_and_counts(b_or=None):
     want, wcnt = oracle.fused_path(g, masks, k, 3, 0)
     assert np.array_equal(to_np(cnt), wcnt) and int(wcnt.max()) == 255
     assert rel_l2(to_np(out), want) <= TOL["f32"]
+
+
+def test_loss_propagation_ring_vs_direct():
+    """Synthetic stand-in for the topology comparison of Sec. 5.3 (Ring has several times the MSE of TAR at
+    the same loss; Sec. 3.1.1 gives the reason: in a ring the partial aggregate travels hop by hop, so one
+    lost packet takes with it everything aggregated so far, while TAR's owner hears from every peer
+    directly).  Same per-transfer packet loss for both; the ring is emulated, generously, with the
+    count-carrying pair reduction (a hop whose packet is lost restarts from the receiver's own entries).
+    Every aggregate is checked against the oracle; the ordering of the errors is the property."""
+    import paper_2310_06993_amd.binding as b
+    import oracle
+    from _util import pack_mask_np, masks_to_dev, to_np, rel_l2, TOL
+    N, L, packet, p = 8, 1 << 20, 256, 0.05
+    rng = np.random.default_rng(2310)
+    g = (rng.standard_normal((N, L)) * 1e-3).astype(np.float32)
+    truth = g.astype(np.float64).mean(axis=0)
+
+    def arrivals(rows):
+        a = rng.random((rows, L // packet)) >= p
+        return np.repeat(a, packet, axis=1)
+
+    # TAR, first stage at the owner (node 0): N - 1 direct transfers, the owner's own shard is local
+    recv = arrivals(N)
+    recv[0] = True
+    m_tar = pack_mask_np(recv)
+    gd = torch.from_numpy(g).to(dev())
+    total = torch.empty(L, device=dev())
+    cnt = torch.empty(L, dtype=torch.uint8, device=dev())
+    mean_tar = torch.empty(L, device=dev())
+    b.or_masked_reduce(gd, masks_to_dev(m_tar), N, L, total, cnt)
+    b.or_finalize(total, cnt, L, mean_tar)
+    w_total, w_cnt = oracle.masked_reduce(g, m_tar)
+    assert np.array_equal(to_np(cnt), w_cnt) and rel_l2(to_np(total), w_total) <= TOL["f32"]
+    assert rel_l2(to_np(mean_tar), oracle.finalize(w_total, w_cnt)) <= TOL["f32"]
+
+    # Ring: the partial for shard 0 starts at node 1 and visits 2, 3, ..., N-1, 0
+    ones = np.ones((1, L), bool)
+    one_count = torch.ones(L, dtype=torch.uint8, device=dev())
+    part_sum, part_cnt = gd[1].clone(), one_count.clone()
+    o_sum, o_cnt = g[1].copy(), np.ones(L, np.uint8)
+    for node in list(range(2, N)) + [0]:
+        m = pack_mask_np(np.concatenate([arrivals(1), ones]))
+        sums = torch.stack([part_sum, gd[node]])
+        counts = torch.stack([part_cnt, one_count])
+        new_sum, new_cnt = torch.empty(L, device=dev()), torch.empty(L, dtype=torch.uint8, device=dev())
+        b.or_masked_reduce_pairs(sums, counts, masks_to_dev(m), 2, L, new_sum, new_cnt)
+        o_sum, o_cnt = oracle.masked_reduce_pairs(np.stack([o_sum, g[node]]), np.stack([o_cnt, np.ones(L, np.uint8)]), m)
+        assert np.array_equal(to_np(new_cnt), o_cnt) and rel_l2(to_np(new_sum), o_sum) <= TOL["f32"]
+        part_sum, part_cnt = new_sum, new_cnt
+    mean_ring = torch.empty(L, device=dev())
+    b.or_finalize(part_sum, part_cnt, L, mean_ring)
+    assert rel_l2(to_np(mean_ring), oracle.finalize(o_sum, o_cnt)) <= TOL["f32"]
+
+    mse_tar = float(((to_np(mean_tar).astype(np.float64) - truth) ** 2).mean())
+    mse_ring = float(((to_np(mean_ring).astype(np.float64) - truth) ** 2).mean())
+    # expected contributions lost per entry: (N-1) p directly, about p N (N-1) / 2 along the ring
+    assert mse_ring > 2.5 * mse_tar > 0
+    assert int(part_cnt.min()) >= 1 and int(cnt.min()) >= 1
