@@ -135,6 +135,19 @@ __global__ __launch_bounds__(256) void k_finalize(const float* __restrict__ sum,
 
 __global__ void k_zero_u64(unsigned long long* p) { *p = 0; }
 
+// Sign bits of n_counters * 128 consecutive entries as a table: the Philox output for counter
+// first_counter + c, 16 bytes, at tab + 16 c -- so bit j of 64-bit word w is the sign of entry 64 w + j
+// counted from the first entry.  The fused kernels for blocks above 2^14 read it with scalar loads.
+__global__ __launch_bounds__(256) void k_sign_table(uint4* __restrict__ tab, u64 seed, u64 first_counter,
+                                                    u64 n_counters) {
+  const u64 c = (u64)blockIdx.x * 256 + threadIdx.x;
+  if (c >= n_counters) return;
+  const u64 ctr = first_counter + c;
+  const ordev::u32x4 w =
+      ordev::philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), 0u, 0u, (uint32_t)seed, (uint32_t)(seed >> 32));
+  tab[c] = make_uint4(w.a, w.b, w.c, w.d);
+}
+
 // Sec. 3.4 loss monitoring: total of the received counts of a shard (16 counts per lane, byte sums
 // with v_sad_u8, one 64-bit atomic per wavefront)
 __global__ __launch_bounds__(256) void k_received_total(const uint8_t* __restrict__ count, u64 L,
@@ -372,9 +385,16 @@ or_status run_path(bool fused, const T* in, const uint32_t* masks, int N, u64 L,
   d.in = ws_f32;
   d.unit0 = units;   // shards hold whole blocks: no tile of the decode needs bounds checks
   if (fused) {
+    // the sign table takes the part of the workspace that the unfused path uses for counts (L/8 of its L bytes)
+    const u64 counters = L >> 7;
+    if ((counters + 255) / 256 > 0x7FFFFFFFull) return OR_ERR_SHAPE;
+    if (hipError_t e = orhost::launch_kernel(k_sign_table, dim3((unsigned)((counters + 255) / 256)), dim3(256), s,
+                                             orhost::LAUNCH_FIRST, (uint4*)ws_cnt, seed, base >> 7, counters))
+      return finish(e);
+    a.sign_tab = (const u64*)ws_cnt;
     a.mean_out = ws_f32;
     a.out = nullptr;
-    if (hipError_t e = (bf16 ? t->fused_bf16 : t->fused_f32)(a, units, s, orhost::LAUNCH_FIRST)) return finish(e);
+    if (hipError_t e = (bf16 ? t->fused_bf16 : t->fused_f32)(a, units, s, 0)) return finish(e);
     return finish((bf16 ? t->decode_bf16 : t->decode_f32)(d, units, s, orhost::LAUNCH_LAST));
   }
   uint8_t* cnt = count_out ? count_out : ws_cnt;

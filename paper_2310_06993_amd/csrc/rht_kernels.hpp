@@ -12,6 +12,7 @@ struct PathArgs {
   void* out;               // result vector
   uint8_t* count_out;      // may be null
   float* mean_out;         // fused without decode: mean in the encoded domain, fp32
+  const u64* sign_tab;     // fused, blocks above 2^14: sign bits of the shard's entries, 64 per word (see k_fused_pairs)
   u64 n;                   // valid entries of the input (encode) / output (decode)
   u64 n_pad;               // padded length = vector length on the encoded side; shard_len for reduce/fused
   u64 seed;
@@ -342,9 +343,13 @@ __device__ __forceinline__ void fused_tile(const PathArgs& a, u64 unit) {
     transform<K, true, NB != 2>(va, xbuf[NB == 2 ? flip : 0], wave, lane, kt);
     flip ^= 1;
     if (sizeof(In) == 2) {
-      const float pre = scale_first ? a.scale : 1.0f;
+      if (scale_first) {
 #pragma unroll
-      for (int r = 0; r < R; ++r) va[r] = round_to<In>(va[r] * pre);
+        for (int r = 0; r < R; ++r) va[r] = round_to<In>(va[r] * a.scale);
+      } else {
+#pragma unroll
+        for (int r = 0; r < R; ++r) va[r] = round_to<In>(va[r]);
+      }
     }
     masked_accumulate(va, ma, acc, cnt, full);
     if (i + 1 < a.N) {
@@ -407,11 +412,6 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_fused_pairs(PathArgs a) {
   const int moff = mask_word_offset<K>(wave, lane);
   const u64 mrow = L >> 5;
 
-  uint32_t sw[PARTS];
-#pragma unroll
-  for (int q = 0; q < PARTS; ++q)
-    sw[q] = sign_words<R>(a.seed, a.base + (t0 + q) * T + (u64)wave * Geo<K>::WAVE_ENTRIES);
-
   float acc_lo[R], acc_hi[R];
   uint32_t cnt_lo[R / 4], cnt_hi[R / 4];
   int full_lo = 0, full_hi = 0;
@@ -420,13 +420,18 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_fused_pairs(PathArgs a) {
 #pragma unroll
   for (int r = 0; r < R / 4; ++r) cnt_lo[r] = cnt_hi[r] = 0;
 
-  // dst (+)= coef * (signed t)
-  auto add_signed = [&](float (&dst)[R], const float (&t)[R], uint32_t words, float coef, bool first) {
-    uint32_t w = words;
-    asm volatile("" : "+v"(w));   // the lane masks of a tile are formed where the tile is used, not hoisted
+  // dst (+)= coef * (signed t), t = input tile q.  The sign bits come from a table that a small kernel
+  // wrote before this one (a.sign_tab: bit j of word w = entry 64w + j of the shard): the R words of this
+  // wavefront's registers are scalar loads that land in scalar register pairs and serve as lane masks as
+  // they are.  Forming them from Philox words held in a vector register instead costs two v_readlane per
+  // register and worker -- measured, a fifth of this kernel's vector-ALU time.
+  typedef const u64 __attribute__((address_space(4))) * table_ptr;
+  auto add_signed = [&](float (&dst)[R], const float (&t)[R], int q, float coef, bool first) {
+    table_ptr sg = (table_ptr)(a.sign_tab + ((((t0 + q) * T) + (u64)wave * Geo<K>::WAVE_ENTRIES) >> 6));
+    asm volatile("" : "+s"(sg));   // the words of a tile are loaded where the tile is used, not hoisted
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      const float ts = in_mask(mask_of_reg(w, r)) ? -t[r] : t[r];
+      const float ts = in_mask(sg[r]) ? -t[r] : t[r];
       dst[r] = first ? coef * ts : __builtin_fmaf(coef, ts, dst[r]);
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -435,9 +440,13 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_fused_pairs(PathArgs a) {
                          int& full) {
     transform<K, true, false>(v, buf, wave, lane, kt);
     if (sizeof(In) == 2) {
-      const float pre = scale_first ? a.scale : 1.0f;
+      if (scale_first) {
 #pragma unroll
-      for (int r = 0; r < R; ++r) v[r] = round_to<In>(v[r] * pre);
+        for (int r = 0; r < R; ++r) v[r] = round_to<In>(v[r] * a.scale);
+      } else {
+#pragma unroll
+        for (int r = 0; r < R; ++r) v[r] = round_to<In>(v[r]);
+      }
     }
     masked_accumulate(v, m, acc, cnt, full);
   };
@@ -451,13 +460,13 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_fused_pairs(PathArgs a) {
     load_tile<K, false, true>(x, (t0 + HP) * T, L, wave, lane, C);
     const uint32_t m_lo = load_mask_words<K, true>(a.masks + (u64)i * mrow, e_lo, L, moff);
     const uint32_t m_hi = load_mask_words<K, true>(a.masks + (u64)i * mrow, e_hi, L, moff);
-    add_signed(A, A, sw[0], 1.0f, true);
+    add_signed(A, A, 0, 1.0f, true);
     if constexpr (HP == 2) {
-      add_signed(A, t, sw[1], part_coef(h, 1), false);
+      add_signed(A, t, 1, part_coef(h, 1), false);
       load_tile<K, false, true>(x, (t0 + HP + 1) * T, L, wave, lane, t);
     }
-    add_signed(C, C, sw[HP], 1.0f, true);
-    if constexpr (HP == 2) add_signed(C, t, sw[HP + 1], part_coef(h, 1), false);
+    add_signed(C, C, HP, 1.0f, true);
+    if constexpr (HP == 2) add_signed(C, t, HP + 1, part_coef(h, 1), false);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       w[r] = A[r] + C[r];
