@@ -303,8 +303,26 @@ def main():
                                   "entries_per_s": ent / ps, "ms_per_step": ps * 1e3, "avg_launch_us": kn * 1e6,
                                   "launch_GB_per_s": by / kn / 1e9, "frac_hbm_peak": by / kn / 1e9 / HBM_PEAK_GBPS,
                                   "input_sets_rotated": ns, "note": note})
-                    # the same buckets through the batched entry point: 32 buckets per launch
+                    # the same per-bucket launches spread over four streams: a bucket alone is ~100
+                    # workgroups, so kernels of different buckets share the GPU (what a DDP hook that
+                    # fires per bucket can do without waiting for the other buckets)
+                    streams = [torch.cuda.Stream() for _ in range(4)]
                     Lb = c.shard_len(c.bucket_entries)
+                    def spread(nsteps):
+                        for j in range(nsteps * nb):
+                            with torch.cuda.stream(streams[j % 4]):
+                                launch(b, c, Lb, st[j % ns], j % ns % c.workers)
+                    spread(1)
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    spread(steps)
+                    torch.cuda.synchronize()
+                    ps4 = (time.perf_counter() - t0) / steps
+                    extra.append({"workload": name + " (one launch per bucket, four streams)",
+                                  "GB_per_s": by_step / ps4 / 1e9, "entries_per_s": ent / ps4, "ms_per_step": ps4 * 1e3,
+                                  "frac_hbm_peak": by_step / ps4 / 1e9 / HBM_PEAK_GBPS, "input_sets_rotated": ns,
+                                  "note": "%d launches per step, round-robin over 4 streams" % nb})
+                    # the same buckets through the batched entry point: 32 buckets per launch
                     arr = b.make_buckets([(st[j % ns][0], st[j % ns][1], st[j % ns][2], st[j % ns][3], Lb, c.seed,
                                            (j % ns % c.workers) * Lb) for j in range(nb)])
                     for _ in range(2):
