@@ -13,15 +13,20 @@ constexpr int K = OR_K;
 typedef Geo<K> G;
 
 #define OR_LAUNCHER(name, kernel)                                                            \
-  /* serves output tiles a.unit0 .. a.unit0 + units - 1 */                                  \
+  /* serves output tiles a.unit0 .. a.unit0 + units - 1, one workgroup per tile */          \
   hipError_t name(const PathArgs& a, unsigned long long units, hipStream_t s, int pos) {    \
     if (units == 0) return hipSuccess;                                                       \
-    PathArgs b = a;                                                                          \
-    b.unit_end = a.unit0 + units;                                                            \
-    unsigned long long grid = units;                                                         \
-    if (G::PARTS > 1) grid = (units + 8 * G::PARTS - 1) / (8 * G::PARTS) * (8 * G::PARTS);   \
-    if (grid > 0x7FFFFFFFull) return hipErrorInvalidValue;                                   \
-    return launch_kernel(kernel, dim3((unsigned)grid), dim3(G::THREADS), s, pos, b);         \
+    if (units > 0x7FFFFFFFull) return hipErrorInvalidValue;                                  \
+    return launch_kernel(kernel, dim3((unsigned)units), dim3(G::THREADS), s, pos, a);        \
+  }
+
+// blocks above 2^14: one workgroup per block of G::PARTS tiles; a.unit0 and units count tiles
+#define OR_BLOCK_LAUNCHER(name, kernel)                                                      \
+  hipError_t name(const PathArgs& a, unsigned long long units, hipStream_t s, int pos) {    \
+    const unsigned long long blocks = units >> G::HB;                                        \
+    if (blocks == 0) return hipSuccess;                                                      \
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;                                 \
+    return launch_kernel(kernel, dim3((unsigned)blocks), dim3(G::THREADS), s, pos, a);       \
   }
 
 #define OR_BATCH_LAUNCHER(name, kernel)                                                       \
@@ -31,9 +36,9 @@ typedef Geo<K> G;
     return launch_kernel(kernel, dim3((unsigned)units), dim3(G::THREADS), s, pos, a);        \
   }
 
-#define OR_SPLIT_LAUNCHER(name, kernel_full, kernel_tail)                                    \
-  OR_LAUNCHER(name##_full, kernel_full)                                                      \
-  OR_LAUNCHER(name##_tail, kernel_tail)                                                      \
+#define OR_SPLIT_LAUNCHER(name, LAUNCHER, kernel_full, kernel_tail)                          \
+  LAUNCHER(name##_full, kernel_full)                                                         \
+  LAUNCHER(name##_tail, kernel_tail)                                                         \
   /* a.unit0 = number of leading tiles that need no bounds checks; the rest go to the checked kernel */ \
   hipError_t name(const PathArgs& a, unsigned long long units, hipStream_t s, int pos) {    \
     const unsigned long long nfull = a.unit0 < units ? a.unit0 : units, ntail = units - nfull; \
@@ -49,14 +54,23 @@ typedef Geo<K> G;
     return hipSuccess;                                                                       \
   }
 
-OR_SPLIT_LAUNCHER(enc_f32, (k_encode<K, float, float, true>), (k_encode<K, float, float, false>))
-OR_SPLIT_LAUNCHER(enc_bf16, (k_encode<K, bf16_t, bf16_t, true>), (k_encode<K, bf16_t, bf16_t, false>))
-OR_SPLIT_LAUNCHER(dec_f32, (k_decode<K, float, false, true>), (k_decode<K, float, false, false>))
-OR_SPLIT_LAUNCHER(dec_bf16, (k_decode<K, bf16_t, false, true>), (k_decode<K, bf16_t, false, false>))
-OR_SPLIT_LAUNCHER(fdec_f32, (k_decode<K, float, true, true>), (k_decode<K, float, true, false>))
-OR_SPLIT_LAUNCHER(fdec_bf16, (k_decode<K, bf16_t, true, true>), (k_decode<K, bf16_t, true, false>))
-OR_SPLIT_LAUNCHER(mdec_f32, (k_decode<K, float, false, true, true>), (k_decode<K, float, false, false, true>))
-OR_SPLIT_LAUNCHER(mdec_bf16, (k_decode<K, bf16_t, false, true, true>), (k_decode<K, bf16_t, false, false, true>))
+#if OR_K <= 14
+#define OR_ENC(In, Wire, FULL) (k_encode<K, In, Wire, FULL>)
+#define OR_DEC(Out, FIN, FULL, MASKED) (k_decode<K, Out, FIN, FULL, MASKED>)
+#define OR_XFORM_LAUNCHER OR_LAUNCHER
+#else
+#define OR_ENC(In, Wire, FULL) (k_encode_block<K, In, Wire, FULL>)
+#define OR_DEC(Out, FIN, FULL, MASKED) (k_decode_block<K, Out, FIN, FULL, MASKED>)
+#define OR_XFORM_LAUNCHER OR_BLOCK_LAUNCHER
+#endif
+OR_SPLIT_LAUNCHER(enc_f32, OR_XFORM_LAUNCHER, OR_ENC(float, float, true), OR_ENC(float, float, false))
+OR_SPLIT_LAUNCHER(enc_bf16, OR_XFORM_LAUNCHER, OR_ENC(bf16_t, bf16_t, true), OR_ENC(bf16_t, bf16_t, false))
+OR_SPLIT_LAUNCHER(dec_f32, OR_XFORM_LAUNCHER, OR_DEC(float, false, true, false), OR_DEC(float, false, false, false))
+OR_SPLIT_LAUNCHER(dec_bf16, OR_XFORM_LAUNCHER, OR_DEC(bf16_t, false, true, false), OR_DEC(bf16_t, false, false, false))
+OR_SPLIT_LAUNCHER(fdec_f32, OR_XFORM_LAUNCHER, OR_DEC(float, true, true, false), OR_DEC(float, true, false, false))
+OR_SPLIT_LAUNCHER(fdec_bf16, OR_XFORM_LAUNCHER, OR_DEC(bf16_t, true, true, false), OR_DEC(bf16_t, true, false, false))
+OR_SPLIT_LAUNCHER(mdec_f32, OR_XFORM_LAUNCHER, OR_DEC(float, false, true, true), OR_DEC(float, false, false, true))
+OR_SPLIT_LAUNCHER(mdec_bf16, OR_XFORM_LAUNCHER, OR_DEC(bf16_t, false, true, true), OR_DEC(bf16_t, false, false, true))
 #if OR_K <= 14
 OR_LAUNCHER(rdec_f32, (k_reduce_decode<K, float, float>))
 OR_LAUNCHER(rdec_bf16, (k_reduce_decode<K, bf16_t, bf16_t>))

@@ -18,7 +18,6 @@ struct PathArgs {
   u64 seed;
   u64 base;                // index of entry 0 in the sign stream
   u64 unit0;               // first output tile served by this launch
-  u64 unit_end;            // one past the last output tile served by this launch (set by the launcher)
   int N;                   // workers
   int k;                   // block_log2
   float scale;             // 2^(-k/2) rounded to fp32
@@ -29,86 +28,55 @@ template <int K> constexpr bool kShardTilesFull = (K != 0);
 // LDS buffers for the exchange: two (one barrier per exchange) while they fit several workgroups per CU.
 template <int K> constexpr int kXbufs = (Geo<K>::Q == 0) ? 0 : (Geo<K>::T * 4 <= 16384 ? 2 : 1);
 
-// Which output tile a workgroup serves.  When a block spans PARTS tiles, the PARTS workgroups of one block
-// all read the same input tiles; consecutive workgroup ids go round-robin over the 8 XCDs (each with its
-// own L2), so the ids are remapped to put a block's workgroups on ONE XCD, next to each other in dispatch
-// order.  The launcher rounds the grid up to a multiple of 8*PARTS; ids that map at or past `unit_end`
-// (the end of THIS launch's range, not of the vector) return `none`.
-template <int K>
-__device__ __forceinline__ u64 unit_of_workgroup(u64 unit0, u64 unit_end, bool& none) {
-  constexpr int HB = Geo<K>::HB, PARTS = Geo<K>::PARTS;
-  none = false;
-  if constexpr (PARTS == 1) {
-    return unit0 + blockIdx.x;
-  } else {
-    const u64 x = blockIdx.x, slot = x >> 3;
-    const u64 blk = ((slot >> HB) << 3) + (x & 7);
-    const u64 unit = unit0 + (blk << HB) + (slot & (PARTS - 1));
-    none = unit >= unit_end;
-    return unit;
-  }
-}
-
 // +1/-1 entry of H_{2^HB}: row `part`, column q
 __device__ __forceinline__ float part_coef(int part, int q) { return (__builtin_popcount(part & q) & 1) ? -1.0f : 1.0f; }
 
 template <int K>
 __device__ __forceinline__ int tile_bits(int k) { return K ? Geo<K>::KT : k; }
 
-// Sign words (see sign_words) of the PARTS input tiles that feed output tile `unit`; blocks above 2^14 only.
+// ---- blocks above 2^14: one workgroup per block in encode / decode ----------------------------------
+// H_{2^k} = H_{2^(k-14)} (x) H_{2^14}: a workgroup holds the block's PARTS tiles in registers (PARTS*R per
+// lane), runs the small factor as add/sub between the tiles and the big one tile by tile.  Every input is
+// read once and gets its sign once; one Philox evaluation per wavefront covers its part of all the tiles.
+
+// Sign bits of this wavefront's registers in all PARTS tiles of a block, as two vector registers: lane
+// q*16 + r holds the 64-bit lane mask of register r of tile q (lo, hi).  `g` = index, in the padded
+// vector, of this wavefront's first entry in tile 0 of the block.
 template <int K>
-__device__ __forceinline__ void part_sign_words(u64 unit, u64 seed, u64 base, int wave, uint32_t (&sw)[Geo<K>::PARTS]) {
-  constexpr int T = Geo<K>::T, HB = Geo<K>::HB, PARTS = Geo<K>::PARTS;
-  const u64 blk = unit >> HB;
-#pragma unroll
-  for (int q = 0; q < PARTS; ++q)
-    sw[q] = sign_words<Geo<K>::R>(seed, base + ((blk << HB) + q) * T + (u64)wave * Geo<K>::WAVE_ENTRIES);
+__device__ __forceinline__ void block_sign_words(u64 seed, u64 g, uint32_t& lo, uint32_t& hi) {
+  static_assert(Geo<K>::R == 16 && Geo<K>::PARTS <= 4, "lane q*16 + r");
+  const int l = lane_id(), q = l >> 4, r = l & 15;
+  const u64 ctr = ((g + (u64)q * Geo<K>::T) >> 7) + (u64)(r >> 1);   // a counter covers two registers
+  const u32x4 w = philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), 0u, 0u, (uint32_t)seed, (uint32_t)(seed >> 32));
+  lo = (r & 1) ? w.c : w.a;
+  hi = (r & 1) ? w.d : w.b;
 }
-
-// v = sum over the block's PARTS input tiles q of H_{PARTS}[part][q] * (signed tile q), layout A
-template <int K, bool ALL_FULL, class In>
-__device__ __forceinline__ void combine_parts(const In* __restrict__ x, u64 limit, u64 blk, int part, int wave, int lane,
-                                              float (&v)[Geo<K>::R], const uint32_t (&sw)[Geo<K>::PARTS]) {
-  constexpr int T = Geo<K>::T, HB = Geo<K>::HB, PARTS = Geo<K>::PARTS, R = Geo<K>::R;
-  // tile q+1 is in flight while tile q is signed and added
-  float ta[R], tb[R];
-  auto add_tile = [&](const float (&t)[R], int q) {
-    const float c = part_coef(part, q);
-    uint32_t w = sw[q];
-    asm volatile("" : "+v"(w));   // keeps the lane masks of tile q from being formed before tile q is reached
+template <int NR>
+__device__ __forceinline__ void apply_block_signs(float (&v)[NR], uint32_t lo, uint32_t hi, int q) {
+  asm volatile("" : "+v"(lo), "+v"(hi));   // the lane masks of a tile are formed where the tile is used
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      const float ts = in_mask(mask_of_reg(w, r)) ? -t[r] : t[r];
-      v[r] = q == 0 ? c * ts : __builtin_fmaf(c, ts, v[r]);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-  };
-  load_tile<K, false, ALL_FULL>(x, (blk << HB) * T, limit, wave, lane, ta);
-#pragma unroll
-  for (int q = 0; q < PARTS; q += 2) {
-    load_tile<K, false, ALL_FULL>(x, ((blk << HB) + q + 1) * T, limit, wave, lane, tb);
-    add_tile(ta, q);
-    if (q + 2 < PARTS) load_tile<K, false, ALL_FULL>(x, ((blk << HB) + q + 2) * T, limit, wave, lane, ta);
-    add_tile(tb, q + 1);
+  for (int r = 0; r < NR; ++r) {
+    const u64 m = (u64)(uint32_t)__builtin_amdgcn_readlane((int)lo, q * 16 + r) |
+                  ((u64)(uint32_t)__builtin_amdgcn_readlane((int)hi, q * 16 + r) << 32);
+    v[r] = in_mask(m) ? -v[r] : v[r];
   }
+  __builtin_amdgcn_sched_barrier(0);
 }
-
-// Raw tile of one worker in layout A.  One tile per block: the plain tile, signs still to be applied by
-// the caller.  Blocks above 2^14: the signed +-1 combination of the block's PARTS tiles that feeds output
-// tile `unit` (H_{2^k} = H_{2^(k-14)} (x) H_{2^14}), with the signs taken from `sw`.
-template <int K, bool FULL, class In>
-__device__ __forceinline__ void load_raw_tile(const In* __restrict__ x, u64 limit, u64 unit, int wave, int lane,
-                                              float (&v)[Geo<K>::R], const uint32_t (&sw)[Geo<K>::PARTS]) {
-  constexpr int T = Geo<K>::T, HB = Geo<K>::HB, PARTS = Geo<K>::PARTS, R = Geo<K>::R;
-  if constexpr (PARTS == 1) {
-    load_tile<K, false, FULL>(x, unit * T, limit, wave, lane, v);
-  } else {
-    const u64 blk = unit >> HB;
-    const int part = (int)(unit & (PARTS - 1));
-    // one decision for the whole block keeps each branch straight-line code
-    if (FULL || ((blk + 1) << HB) * T <= limit) combine_parts<K, true>(x, limit, blk, part, wave, lane, v, sw);
-    else combine_parts<K, false>(x, limit, blk, part, wave, lane, v, sw);
-  }
+// the factor H_{PARTS} across the tiles, in place
+template <int PARTS, int NR>
+__device__ __forceinline__ void across_tiles(float (&v)[PARTS][NR]) {
+#pragma unroll
+  for (int s = 1; s < PARTS; s <<= 1)
+#pragma unroll
+    for (int q = 0; q < PARTS; ++q)
+      if ((q & s) == 0) {
+#pragma unroll
+        for (int r = 0; r < NR; ++r) {
+          const float x = v[q][r], y = v[q + s][r];
+          v[q][r] = x + y;
+          v[q + s][r] = x - y;
+        }
+      }
 }
 
 // Sec. 3.3 encode: out = B^(-1/2) H D x, blockwise; pad of the last block is zero.
@@ -118,25 +86,48 @@ __device__ __forceinline__ void load_raw_tile(const In* __restrict__ x, u64 limi
 template <int K, class In, class Wire, bool FULL>
 __global__ __launch_bounds__(Geo<K>::THREADS) void k_encode(PathArgs a) {
   constexpr int T = Geo<K>::T, R = Geo<K>::R;
+  static_assert(Geo<K>::PARTS == 1, "larger blocks use k_encode_block");
   __shared__ float xbuf[Geo<K>::Q > 0 ? T : 1];
   const int wave = wave_id(), lane = lane_id(), kt = tile_bits<K>(a.k);
-  bool none;
-  const u64 unit = unit_of_workgroup<K>(a.unit0, a.unit_end, none);
-  if (none) return;
+  const u64 unit = a.unit0 + blockIdx.x;
   float v[R];
-  uint32_t sw[Geo<K>::PARTS] = {};
-  if constexpr (Geo<K>::PARTS > 1) part_sign_words<K>(unit, a.seed, a.base, wave, sw);
-  load_raw_tile<K, FULL>((const In*)a.in, a.n, unit, wave, lane, v, sw);
-  if constexpr (Geo<K>::PARTS == 1) {
-    u64 sg[R];
-    sign_masks(a.seed, a.base + unit * T + (u64)wave * Geo<K>::WAVE_ENTRIES, sg);
-    apply_signs(v, sg);
-  }
+  load_tile<K, false, FULL>((const In*)a.in, unit * T, a.n, wave, lane, v);
+  u64 sg[R];
+  sign_masks(a.seed, a.base + unit * T + (u64)wave * Geo<K>::WAVE_ENTRIES, sg);
+  apply_signs(v, sg);
   transform<K, true>(v, xbuf, wave, lane, kt);
   const float c = a.scale * lane_sigma(lane, kt < 6 ? kt : 6);
 #pragma unroll
   for (int r = 0; r < R; ++r) v[r] *= c;
   store_tile<K, true, FULL>((Wire*)a.out, unit * T, a.n_pad, wave, lane, v);
+}
+
+// The same for blocks above 2^14: workgroup x encodes block a.unit0 / PARTS + x (a.unit0 counts tiles).
+// FULL = false: the block is cut short by the end of the input (its pad reads as zero); the output always
+// holds whole blocks.
+template <int K, class In, class Wire, bool FULL>
+__global__ __launch_bounds__(Geo<K>::THREADS) void k_encode_block(PathArgs a) {
+  constexpr int T = Geo<K>::T, R = Geo<K>::R, HB = Geo<K>::HB, PARTS = Geo<K>::PARTS;
+  static_assert(PARTS > 1, "blocks above 2^14");
+  __shared__ float xbuf[2][T];   // the registers allow one workgroup per CU anyway: alternate, one barrier per exchange
+  const int wave = wave_id(), lane = lane_id(), kt = Geo<K>::KT;
+  const u64 tile0 = a.unit0 + ((u64)blockIdx.x << HB);
+  float v[PARTS][R];
+#pragma unroll
+  for (int q = 0; q < PARTS; ++q) load_tile<K, false, FULL>((const In*)a.in, (tile0 + q) * T, a.n, wave, lane, v[q]);
+  uint32_t slo, shi;
+  block_sign_words<K>(a.seed, a.base + tile0 * T + (u64)wave * Geo<K>::WAVE_ENTRIES, slo, shi);
+#pragma unroll
+  for (int q = 0; q < PARTS; ++q) apply_block_signs(v[q], slo, shi, q);
+  across_tiles<PARTS, R>(v);
+  const float c = a.scale * lane_sigma(lane, 6);
+#pragma unroll
+  for (int p = 0; p < PARTS; ++p) {
+    transform<K, true, false>(v[p], xbuf[p & 1], wave, lane, kt);
+#pragma unroll
+    for (int r = 0; r < R; ++r) v[p][r] *= c;
+    store_tile<K, true, true>((Wire*)a.out, (tile0 + p) * T, a.n_pad, wave, lane, v[p]);
+  }
 }
 
 // Mean tile (layout B) for decode: either the mean itself, or sum / count with 0 where count is 0
@@ -166,28 +157,13 @@ __device__ __forceinline__ void load_mean_tile(const PathArgs& a, u64 tile, int 
 // Sec. 3.3 / Sec. 4 decode: out = D B^(-1/2) H mean, first n entries kept.
 template <int K, class Out, bool FINALIZE, bool FULL, bool MASKED = false>
 __global__ __launch_bounds__(Geo<K>::THREADS) void k_decode(PathArgs a) {
-  constexpr int T = Geo<K>::T, HB = Geo<K>::HB, PARTS = Geo<K>::PARTS, R = Geo<K>::R;
+  constexpr int T = Geo<K>::T, R = Geo<K>::R;
+  static_assert(Geo<K>::PARTS == 1, "larger blocks use k_decode_block");
   __shared__ float xbuf[Geo<K>::Q > 0 ? T : 1];
   const int wave = wave_id(), lane = lane_id(), kt = tile_bits<K>(a.k);
-  bool none;
-  const u64 unit = unit_of_workgroup<K>(a.unit0, a.unit_end, none);
-  if (none) return;
+  const u64 unit = a.unit0 + blockIdx.x;
   float v[R];
-  if constexpr (PARTS == 1) {
-    load_mean_tile<K, FINALIZE, FULL, MASKED>(a, unit, wave, lane, v);
-  } else {
-    const u64 blk = unit >> HB;
-    const int part = (int)(unit & (PARTS - 1));
-#pragma unroll
-    for (int r = 0; r < R; ++r) v[r] = 0.0f;
-    for (int q = 0; q < PARTS; ++q) {
-      float t[R];
-      load_mean_tile<K, FINALIZE, FULL, MASKED>(a, (blk << HB) + q, wave, lane, t);
-      const float c = part_coef(part, q);
-#pragma unroll
-      for (int r = 0; r < R; ++r) v[r] = __builtin_fmaf(c, t[r], v[r]);
-    }
-  }
+  load_mean_tile<K, FINALIZE, FULL, MASKED>(a, unit, wave, lane, v);
   transform<K, false>(v, xbuf, wave, lane, kt);
   const float c = a.scale * lane_sigma(lane, kt < 6 ? kt : 6);
   u64 sg[R];
@@ -196,6 +172,32 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_decode(PathArgs a) {
   for (int r = 0; r < R; ++r) v[r] *= c;
   apply_signs(v, sg);
   store_tile<K, false, FULL>((Out*)a.out, unit * T, a.n, wave, lane, v);
+}
+
+// The same for blocks above 2^14 (see k_encode_block).  The input holds whole blocks; FULL = false: the
+// output is cut short inside this block.
+template <int K, class Out, bool FINALIZE, bool FULL, bool MASKED = false>
+__global__ __launch_bounds__(Geo<K>::THREADS) void k_decode_block(PathArgs a) {
+  constexpr int T = Geo<K>::T, R = Geo<K>::R, HB = Geo<K>::HB, PARTS = Geo<K>::PARTS;
+  static_assert(PARTS > 1, "blocks above 2^14");
+  __shared__ float xbuf[2][T];
+  const int wave = wave_id(), lane = lane_id(), kt = Geo<K>::KT;
+  const u64 tile0 = a.unit0 + ((u64)blockIdx.x << HB);
+  float v[PARTS][R];
+#pragma unroll
+  for (int q = 0; q < PARTS; ++q) load_mean_tile<K, FINALIZE, true, MASKED>(a, tile0 + q, wave, lane, v[q]);
+  uint32_t slo, shi;
+  block_sign_words<K>(a.seed, a.base + tile0 * T + (u64)wave * Geo<K>::WAVE_ENTRIES, slo, shi);
+  across_tiles<PARTS, R>(v);
+  const float c = a.scale * lane_sigma(lane, 6);
+#pragma unroll
+  for (int p = 0; p < PARTS; ++p) {
+    transform<K, false, false>(v[p], xbuf[p & 1], wave, lane, kt);
+#pragma unroll
+    for (int r = 0; r < R; ++r) v[p][r] *= c;
+    apply_block_signs(v[p], slo, shi, p);
+    store_tile<K, false, FULL>((Out*)a.out, (tile0 + p) * T, a.n, wave, lane, v[p]);
+  }
 }
 
 // acc += value where the worker's copy arrived.  Arrivals are counted as `full` (workers whose whole

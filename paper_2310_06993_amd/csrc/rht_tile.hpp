@@ -134,19 +134,6 @@ __device__ __forceinline__ void sign_masks(u64 seed, u64 g, u64 (&sg)[NR]) {
   }
 }
 
-// The same sign bits as one vector register: lane l holds 32-bit word l of the 2*NR words that cover the
-// wavefront's NR registers (word 2r, 2r+1 = the lane mask of register r), in the format of
-// load_mask_words, so mask_of_reg() turns it into lane masks.  Used where several input tiles each need
-// their own signs and scalar registers cannot hold them all.
-template <int NR>
-__device__ __forceinline__ uint32_t sign_words(u64 seed, u64 g) {
-  const int l = lane_id() & (2 * NR - 1);
-  u64 ctr = (g >> 7) + (u64)(l >> 2);
-  u32x4 w = philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), 0u, 0u, (uint32_t)seed, (uint32_t)(seed >> 32));
-  const int c = l & 3;
-  return c == 0 ? w.a : (c == 1 ? w.b : (c == 2 ? w.c : w.d));
-}
-
 __device__ __forceinline__ bool in_mask(u64 m) { return __builtin_amdgcn_inverse_ballot_w64(m); }
 
 template <int NR>
@@ -345,24 +332,6 @@ __device__ __forceinline__ void load_tile(const T* __restrict__ p, u64 e0, u64 l
 #pragma unroll
     for (int r = 0; r < R; ++r)
       v[r] = buf_load(rs, (LAYOUT_B ? off_b<K>(wave, r) : off_a<K>(wave, r)) + lane, (const T*)nullptr);
-  }
-}
-
-// Registers R0 .. R0+NR-1 of a tile only (same addressing as load_tile).
-template <int K, bool LAYOUT_B, bool FULL, int R0, int NR, class T>
-__device__ __forceinline__ void load_tile_regs(const T* __restrict__ p, u64 e0, u64 limit, int wave, int lane,
-                                               float (&v)[NR]) {
-  if (FULL || e0 + Geo<K>::T <= limit) {
-    const T* q = p + e0;
-    const unsigned l = (unsigned)lane;
-#pragma unroll
-    for (int r = 0; r < NR; ++r)
-      v[r] = to_f32((q + (LAYOUT_B ? off_b<K>(wave, R0 + r) : off_a<K>(wave, R0 + r)))[l]);
-  } else {
-    const __amdgpu_buffer_rsrc_t rs = tile_rsrc(p, e0, limit);
-#pragma unroll
-    for (int r = 0; r < NR; ++r)
-      v[r] = buf_load(rs, (LAYOUT_B ? off_b<K>(wave, R0 + r) : off_a<K>(wave, R0 + r)) + lane, (const T*)nullptr);
   }
 }
 
