@@ -390,8 +390,9 @@ template <int K, class In>
 __global__ __launch_bounds__(Geo<K>::THREADS) void k_fused_pairs(PathArgs a) {
   constexpr int T = Geo<K>::T, R = Geo<K>::R, HB = Geo<K>::HB, PARTS = Geo<K>::PARTS, HP = PARTS / 2;
   static_assert(PARTS == 2 || PARTS == 4, "two or four tiles per block");
-  // registers allow one workgroup per CU, so a second exchange buffer is free and saves a barrier per exchange
-  __shared__ float xbuf[2][T];
+  // bound by the vector ALUs: the transform with lane bits 2..5 turned into register bits (rht_tile.hpp)
+  __shared__ float tbuf[TR_FLOATS];
+  __shared__ float xbuf[TX_FLOATS];
   const int wave = wave_id(), lane = lane_id(), kt = Geo<K>::KT;
   const u64 L = a.n_pad, nblocks = L >> K;
   // workgroup -> (block, h); the HP workgroups of a block sit on one XCD, next to each other
@@ -409,7 +410,7 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_fused_pairs(PathArgs a) {
   const u64 t0 = blk << HB;                      // first tile of the block
   const u64 e_lo = (t0 + h) * T, e_hi = (t0 + h + HP) * T;
   const In* grads = (const In*)a.in;
-  const float sigma = lane_sigma(lane, 6);
+  const float sigma = tr_sigma(lane);
   const bool scale_first = sizeof(In) == 2 && (a.k & 1);
   const int moff = mask_word_offset<K>(wave, lane);
   const u64 mrow = L >> 5;
@@ -438,9 +439,8 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_fused_pairs(PathArgs a) {
     }
     __builtin_amdgcn_sched_barrier(0);
   };
-  auto finish_tile = [&](float (&v)[R], float* buf, uint32_t m, float (&acc)[R], uint32_t (&cnt)[R / 4],
-                         int& full) {
-    transform<K, true, false>(v, buf, wave, lane, kt);
+  auto finish_tile = [&](float (&v)[R], uint32_t m, float (&acc)[R], uint32_t (&cnt)[R / 4], int& full) {
+    transform_transposed<K>(v, tbuf, xbuf, wave, lane);
     if (sizeof(In) == 2) {
       if (scale_first) {
 #pragma unroll
@@ -474,8 +474,8 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_fused_pairs(PathArgs a) {
       w[r] = A[r] + C[r];
       C[r] = A[r] - C[r];
     }
-    finish_tile(w, xbuf[0], m_lo, acc_lo, cnt_lo, full_lo);
-    finish_tile(C, xbuf[1], m_hi, acc_hi, cnt_hi, full_hi);
+    finish_tile(w, m_lo, acc_lo, cnt_lo, full_lo);
+    finish_tile(C, m_hi, acc_hi, cnt_hi, full_hi);
   }
   __builtin_amdgcn_sched_barrier(0);
   const float post = sigma * (scale_first ? 1.0f : a.scale);

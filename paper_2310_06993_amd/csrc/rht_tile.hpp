@@ -285,6 +285,53 @@ __device__ __forceinline__ void transform(float (&v)[Geo<K>::R], float* xbuf, in
   }
 }
 
+// ------------------------------------------------------------------ transform with transposed lane bits
+// For tiles of 16 wavefronts x 16 registers (2^14 entries) in kernels that are bound by the vector ALUs.
+// On MI355X a plain add/sub issues at twice the rate of anything with a DPP control, so the stages of lane
+// bits 2..5 cost three times a register stage (and those of bits 4, 5 an LDS-crossbar operation each on
+// top).  Here those four bits are made register bits by a transposition inside the wavefront (through a
+// part of LDS that belongs to the wavefront alone: no barrier) and run as register stages; only lane
+// bits 0, 1 use DPP.  Layout A in, layout B out (the same code would also take layout B to layout A:
+// with 16 wavefronts of 16 registers the exchange is the same map both ways); result on lane l times
+// tr_sigma(l).
+//   1. register stages (entry bits 6..9), DPP stages (bits 0, 1)
+//   2. transposition: register r, lane l  ->  register (l >> 2), lane (l & 3) | (r << 2);
+//      rows of 68 floats make the write (bank 4r + l) and the read (bank 4(l' >> 2) + (l' & 3) + 4r') hit
+//      64 different banks
+//   3. register stages (entry bits 2..5)
+//   4. exchange between wavefronts, written straight to layout-B positions: the value in wavefront w,
+//      register r', lane l' is entry (l' & 3) | (r' << 2) | ((l' >> 2) << 6) | (w << 10) of the tile;
+//      rows of a receiving wavefront are 1028 floats apart for the same reason as above
+//   5. register stages (entry bits 10..13)
+constexpr int TR_ROW = 68, TR_WAVE = 16 * TR_ROW, TR_FLOATS = 16 * TR_WAVE;   // transposition buffer
+constexpr int TX_WAVE = 16 * 64 + 4, TX_FLOATS = 16 * TX_WAVE;                // exchange buffer
+__device__ __forceinline__ float tr_sigma(int lane) { return (__builtin_popcount(lane & 3) & 1) ? -1.0f : 1.0f; }
+
+template <int K>
+__device__ __forceinline__ void transform_transposed(float (&v)[16], float* tbuf, float* xbuf, int wave, int lane) {
+  static_assert(Geo<K>::R == 16 && Geo<K>::W == 16, "16 wavefronts of 16 registers");
+  reg_stages(v, 0, 4);
+  lane_stage<0>(v, lane);
+  lane_stage<1>(v, lane);
+  float* mine = tbuf + wave * TR_WAVE;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) mine[r * TR_ROW + lane] = v[r];
+  __builtin_amdgcn_wave_barrier();   // lanes read what other lanes of this wavefront wrote: keep the order
+  const float* back = mine + (lane >> 2) * TR_ROW + (lane & 3);
+#pragma unroll
+  for (int r = 0; r < 16; ++r) v[r] = back[r * 4];
+  reg_stages(v, 0, 4);
+  __syncthreads();   // the exchange buffer may still be read from the previous exchange
+  float* to = xbuf + (lane >> 2) * TX_WAVE + wave * 64 + (lane & 3);
+#pragma unroll
+  for (int r = 0; r < 16; ++r) to[r * 4] = v[r];
+  __syncthreads();
+  const float* from = xbuf + wave * TX_WAVE + lane;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) v[r] = from[r * 64];
+  reg_stages(v, 0, 4);
+}
+
 // ------------------------------------------------------------------ tile loads / stores
 // `p` points at entry 0 of the vector, `e0` is the tile's first entry, `limit` the number of valid
 // entries of the vector; entries at or beyond `limit` read as zero / are not written.  FULL = true
