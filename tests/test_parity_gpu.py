@@ -231,6 +231,24 @@ def test_reduce_decode_and_fused(b, orc, k, N, blocks, kind):
         assert (to_np(out2) != want).mean() < 0.02
 
 
+@pytest.mark.parametrize("k,N,blocks", [(16, 1, 1), (15, 9, 3), (16, 2, 3), (12, 1, 2), (14, 17, 1)])
+def test_fused_worker_counts_and_64_bit_seeds(b, orc, k, N, blocks):
+    """One worker, odd worker counts, a seed with high bits set, a base index beyond 2^32."""
+    L = blocks << k
+    rng = np.random.default_rng(9000 + 17 * k + N)
+    raw = (rng.standard_normal((N, L)) * 1e-3).astype(np.float32)
+    recv = rng.random((N, L)) > 0.04
+    masks = pack_mask_np(recv)
+    seed, base = 0xF00DFACE12345678, (1 << 33) + 5 * max(1 << k, 128)
+    want, want_count = orc.fused_path(raw, masks, k, seed, base)
+    out = torch.empty(L, device=dev())
+    count = torch.empty(L, dtype=torch.uint8, device=dev())
+    b.or_fused_path(torch.from_numpy(raw).to(dev()), masks_to_dev(masks), N, L, k, seed, base, out, count,
+                    _workspace(b, L, k))
+    assert np.array_equal(to_np(count), want_count)
+    assert rel_l2(to_np(out), want) <= TOL["f32"]
+
+
 def test_three_calls_equal_fused(b, orc):
     from paper_2310_06993_amd import workloads as wl
     cfg = wl.CONFIGS["tiny"]
