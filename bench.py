@@ -322,7 +322,7 @@ def main():
                                   "GB_per_s": by_step / ps4 / 1e9, "entries_per_s": ent / ps4, "ms_per_step": ps4 * 1e3,
                                   "frac_hbm_peak": by_step / ps4 / 1e9 / HBM_PEAK_GBPS, "input_sets_rotated": ns,
                                   "note": "%d launches per step, round-robin over 4 streams" % nb})
-                    # the same buckets through the batched entry point: 32 buckets per launch
+                    # the same buckets through the batched entry point: 64 buckets per launch
                     arr = b.make_buckets([(st[j % ns][0], st[j % ns][1], st[j % ns][2], st[j % ns][3], Lb, c.seed,
                                            (j % ns % c.workers) * Lb) for j in range(nb)])
                     for _ in range(2):
@@ -333,9 +333,9 @@ def main():
                         b.or_fused_path_batched(arr, nb, c.workers, c.block_log2, False)
                     torch.cuda.synchronize()
                     ps = (time.perf_counter() - t0) / steps
-                    kn = ps / -(-nb // 32)
-                    by = by_step / -(-nb // 32)
-                    note = "all %d buckets per step through or_fused_path_batched (%d launches)" % (nb, -(-nb // 32))
+                    kn = ps / -(-nb // 64)
+                    by = by_step / -(-nb // 64)
+                    note = "all %d buckets per step through or_fused_path_batched (%d launches)" % (nb, -(-nb // 64))
                     name = name + " (batched)"
                 else:
                     ps, kn, by, ns, st = time_fused(wl, b, c, device, steps, 2)

@@ -188,7 +188,7 @@ or_status or_masked_reduce_pairs(const float* sums, const uint8_t* counts, const
                                  uint64_t shard_len, float* sum_out, uint8_t* count_out, void* stream);
 
 /* or_fused_path_batched: or_fused_path / or_fused_path_bf16 for several buckets that share N,
- * block_log2 and element type, in as few launches as possible (up to 32 buckets per launch).  A DDP
+ * block_log2 and element type, in as few launches as possible (up to 64 buckets per launch).  A DDP
  * bucket (Sec. 3.1.1 footnote: 25 MB by default) is only about a hundred tiles per shard, far too few
  * to fill the GPU alone.  `buckets` is a HOST array, read before the call returns; the device
  * pointers in it follow the rules of or_fused_path (grads/out are float or bf16 bits per `bf16`).

@@ -490,7 +490,7 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_fused_pairs(PathArgs a) {
 // Several buckets of one launch shape class (same N, block size and type) in ONE launch: small buckets
 // (a 25 MiB DDP bucket is only ~100 tiles per shard) cannot fill 256 CUs on their own.  Descriptors ride
 // in the kernel arguments; workgroup x serves tile x - tile_start[j] of bucket j.
-constexpr int kMaxBatch = 32;
+constexpr int kMaxBatch = 64;   // 64 descriptors keep BatchArgs under the 4 KB of kernel arguments
 struct BucketArgs {
   const void* in;
   const uint32_t* masks;
@@ -504,6 +504,8 @@ struct BatchArgs {
   uint32_t tile_start[kMaxBatch + 1];
   BucketArgs b[kMaxBatch];
 };
+
+static_assert(sizeof(BatchArgs) <= 4096, "kernel arguments are limited to 4 KB");
 
 template <int K, class In>
 __global__ __launch_bounds__(Geo<K>::THREADS) __attribute__((amdgpu_waves_per_eu(Geo<K>::R == 32 ? 4 : 1)))

@@ -352,10 +352,10 @@ def test_errors_leave_outputs_untouched(b):
 
 @pytest.mark.parametrize("k,kind", [(12, "f32"), (10, "bf16"), (16, "f32")])
 def test_batched_buckets_equal_single_calls(b, orc, k, kind):
-    # buckets of different lengths in one call (more than 32 of them for k = 12: several launches)
+    # buckets of different lengths in one call (more than 64 of them for k = 12: several launches)
     B = 1 << k
     N = 4
-    lens = [B * (1 + j % 3) for j in range(35)] if k == 12 else [2 * B, B, 0, 3 * B]
+    lens = [B * (1 + j % 3) for j in range(70)] if k == 12 else [2 * B, B, 0, 3 * B]
     dt = torch.float32 if kind == "f32" else torch.bfloat16
     gen = torch.Generator(device=dev()).manual_seed(k)
     items, singles = [], []
