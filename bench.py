@@ -187,6 +187,15 @@ def cpu_baseline(wl, b, cfg, sets, target_seconds=12.0):
     t_probe, _, _ = run(probe)
     nblocks = int(max(probe, min(L // B, target_seconds / max(t_probe / probe, 1e-9))))
     secs, want, wcnt = run(nblocks)
+    # a sample that the oracle finishes in well under the target is timed over several passes
+    passes = 1
+    if secs < target_seconds / 2:
+        extra = min(64, int(target_seconds / max(secs, 1e-9)) - 1)
+        total = secs
+        for _ in range(extra):
+            total += run(nblocks)[0]
+        passes += extra
+        secs = total / passes
     n = nblocks * B
     got = out[:n].cpu()
     got = (got.view(torch.int16).numpy().view(np.uint16).astype(np.uint32) << 16).view(np.float32) \
@@ -197,9 +206,9 @@ def cpu_baseline(wl, b, cfg, sets, target_seconds=12.0):
     es = 4 if cfg.dtype == "f32" else 2
     return {
         "value": wl.bytes_fused(N, n, es) / secs / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-        "host_cores": os.cpu_count(), "entries_per_s": N * n / secs, "seconds": secs,
-        "sample": "first %d blocks of 2^%d entries x %d workers of the %s workload (%d of %d input entries)"
-                  % (nblocks, k, N, cfg.name, N * n, N * L),
+        "host_cores": os.cpu_count(), "entries_per_s": N * n / secs, "seconds": secs, "passes": passes,
+        "sample": "first %d blocks of 2^%d entries x %d workers of the %s workload (%d of %d input entries), "
+                  "mean of %d passes" % (nblocks, k, N, cfg.name, N * n, N * L, passes),
         "gpu_vs_oracle_rel_l2_on_sample": rel, "counts_bit_exact_on_sample": counts_equal,
     }
 
