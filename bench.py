@@ -42,10 +42,10 @@ def build_sets(wl, b, cfg, device, nsets, entries=None, first=0):
     return sets
 
 
-def launch(b, cfg, L, st, shard):
+def launch(b, cfg, L, st, shard, stream=None):
     g, m, out, cnt, ws = st
     fn = b.or_fused_path if cfg.dtype == "f32" else b.or_fused_path_bf16
-    fn(g, m, cfg.workers, L, cfg.block_log2, cfg.seed, shard * L, out, cnt, ws)
+    fn(g, m, cfg.workers, L, cfg.block_log2, cfg.seed, shard * L, out, cnt, ws, stream)
 
 
 class HipEvents:
@@ -79,10 +79,14 @@ class HipEvents:
             self.hip.hipEventDestroy(z)
 
 
-def time_fused(wl, b, cfg, device, steps, warmup, entries=None, launches_per_step=1, max_bytes=24 << 30):
-    """Times `steps` steps; a step is `launches_per_step` back-to-back launches (buckets) of one shape.
-    Returns (seconds per step by wall clock, mean seconds per launch by HIP events attached to the
-    dispatches, bytes per launch, number of input sets, the sets)."""
+def time_fused(wl, b, cfg, device, steps, warmup, entries=None, launches_per_step=1, max_bytes=24 << 30, info=None):
+    """Times `steps` steps; a step is `launches_per_step` launches (buckets) of one shape, one after the
+    other on one stream.  The launches of the timed region are recorded into ONE HIP graph beforehand
+    (the entry points only enqueue kernels, so they can be captured) and the timed region is one replay of
+    it: the same kernels in the same strict order as plain launches, without the few microseconds that the
+    runtime leaves between two dependent plain launches.  `info`, if given, also receives the plain-launch
+    timing.  Returns (seconds per step by wall clock, mean seconds per launch by two HIP events on the
+    launch stream, bytes per launch, number of input sets, the sets)."""
     L = cfg.shard_len(entries)
     es = 4 if cfg.dtype == "f32" else 2
     per_launch = wl.bytes_fused(cfg.workers, L, es)
@@ -97,20 +101,34 @@ def time_fused(wl, b, cfg, device, steps, warmup, entries=None, launches_per_ste
         it += 1
     torch.cuda.synchronize()
     total = steps * launches_per_step
-    # The timed region: `total` plain launches back to back, bracketed by a synchronise on both sides
-    # (wall clock -> `value`) and by two HIP events recorded on the launch stream (-> mean time per
-    # launch for the roofline; with back-to-back launches the gaps between kernels are negligible).
+
+    def enqueue_all(first):
+        for j in range(first, first + total):
+            launch(b, cfg, L, sets[j % nsets], j % nsets % cfg.workers)
+
+    if info is not None:   # plain launches back to back, for reference
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        enqueue_all(it)
+        torch.cuda.synchronize()
+        info["plain_launches_ms_per_step"] = (time.perf_counter() - t0) / steps * 1e3
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        enqueue_all(it)
+    graph.replay()            # untimed: the first replay uploads the graph
+    torch.cuda.synchronize()
+    # The timed region: exactly `total` launches, bracketed by a synchronise on both sides (wall clock ->
+    # `value`) and by two HIP events recorded on the launch stream (-> mean time per launch for the roofline).
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     e0.record()
-    for j in range(total):
-        launch(b, cfg, L, sets[it % nsets], it % nsets % cfg.workers)
-        it += 1
+    graph.replay()
     e1.record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     kern = e0.elapsed_time(e1) * 1e-3 / total
+    del graph
     return (t1 - t0) / steps, kern, per_launch, nsets, sets
 
 
@@ -233,6 +251,9 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the other model-sized workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--workload", default="resnet50")
+    ap.add_argument("--timed-region-only", action="store_true",
+                    help="only the warm-up and the timed region (for a profiler: every launch of the run is then "
+                         "one of the serialized launches that `value` and `roofline` are about)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three 512 MiB device-to-device copies (a known-size reference for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -261,11 +282,14 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    per_step, kern, nbytes, nsets, sets = time_fused(wl, b, cfg, device, args.steps, args.warmup)
+    only = args.timed_region_only
+    info = None if only else {}
+    per_step, kern, nbytes, nsets, sets = time_fused(wl, b, cfg, device, args.steps, args.warmup, info=info)
     L = cfg.shard_len()
     # make sure the set the oracle is compared with holds this run's output
-    launch(b, cfg, L, sets[0], 0)
-    torch.cuda.synchronize()
+    if not only:
+        launch(b, cfg, L, sets[0], 0)
+        torch.cuda.synchronize()
 
     result = {
         "metric": "GB/s and gradient entries/s, fused RHT+masked reduce; % of HBM peak",
@@ -287,19 +311,20 @@ def main():
                      "frac": nbytes / kern / 1e9 / HBM_PEAK_GBPS, "traffic": profiled_traffic(cfg.name),
                      "kernel": "k_fused" if cfg.block_log2 <= 14 else "k_sign_table + k_fused_pairs + k_decode_block",
                      "avg_launch_us": kern * 1e6},
+        "timed_region": "one replay of a HIP graph holding the %d launches, in order, on one stream" % args.steps,
+        "plain_launches_ms_per_step": None if only else info["plain_launches_ms_per_step"],
     }
-    med, lo = kernel_only_seconds(b, cfg, L, sets)
-    result["roofline"]["kernel_only_us_dispatch_events"] = med * 1e6      # median of 32 single dispatches
-    result["roofline"]["kernel_only_us_dispatch_events_min"] = lo * 1e6
+    if only:
+        print(json.dumps(result))
+        return
     # The same launches when consecutive steps may overlap (independent buckets issued round-robin on
     # four streams): the ramp, tail and gap of single launches then hide under the neighbours.  Reported
     # beside `value`, which keeps the strict one-after-the-other order.
     streams = [torch.cuda.Stream() for _ in range(4)]
     def overlapped(n):
         for j in range(n):
-            with torch.cuda.stream(streams[j % 4]):
-                launch(b, cfg, L, sets[j % nsets], j % nsets % cfg.workers)
-    overlapped(8)
+            launch(b, cfg, L, sets[j % nsets], j % nsets % cfg.workers, streams[j % 4])
+    overlapped(max(args.steps, 200))   # streams that are new to the runtime need a few hundred launches to settle
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     overlapped(args.steps)
@@ -309,6 +334,11 @@ def main():
                               "frac_hbm_peak": nbytes / t4 / 1e9 / HBM_PEAK_GBPS,
                               "note": "steps issued round-robin on four streams, same inputs and launches"}
     result["three_call_path"] = time_three_calls(wl, b, cfg, sets)
+    # last of the measurements on these inputs: dispatches that carry events switch the runtime's queues to a
+    # slower, profiled mode for the rest of the process
+    med, lo = kernel_only_seconds(b, cfg, L, sets)
+    result["roofline"]["kernel_only_us_dispatch_events"] = med * 1e6      # median of 32 single dispatches
+    result["roofline"]["kernel_only_us_dispatch_events_min"] = lo * 1e6
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(wl, b, cfg, sets)
     del sets
@@ -341,8 +371,7 @@ def main():
                     Lb = c.shard_len(c.bucket_entries)
                     def spread(nsteps):
                         for j in range(nsteps * nb):
-                            with torch.cuda.stream(streams[j % 4]):
-                                launch(b, c, Lb, st[j % ns], j % ns % c.workers)
+                            launch(b, c, Lb, st[j % ns], j % ns % c.workers, streams[j % 4])
                     spread(1)
                     torch.cuda.synchronize()
                     t0 = time.perf_counter()
