@@ -115,7 +115,7 @@ def time_fused(wl, b, cfg, device, steps, warmup, entries=None, launches_per_ste
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         enqueue_all(it)
-    graph.replay()            # untimed: the first replay uploads the graph
+    graph.replay()            # untimed: the first replay uploads the graph (and is `steps` more warm-up steps)
     torch.cuda.synchronize()
     # The timed region: exactly `total` launches, bracketed by a synchronise on both sides (wall clock ->
     # `value`) and by two HIP events recorded on the launch stream (-> mean time per launch for the roofline).
