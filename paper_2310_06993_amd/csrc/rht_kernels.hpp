@@ -143,7 +143,7 @@ __device__ __forceinline__ void load_mean_tile(const PathArgs& a, u64 tile, int 
     float c[R];
     load_tile<K, true, FULL>(a.count_in, tile * T, a.n_pad, wave, lane, c);
 #pragma unroll
-    for (int r = 0; r < R; ++r) v[r] = c[r] > 0.0f ? v[r] / c[r] : 0.0f;
+    for (int r = 0; r < R; ++r) v[r] = c[r] > 0.0f ? v[r] * __builtin_amdgcn_rcpf(c[r]) : 0.0f;   // as finalize_mean
   }
   if constexpr (MASKED) {
     const uint32_t w = load_mask_words<K, FULL>(a.masks, tile * T, a.n_pad, mask_word_offset<K>(wave, lane));
