@@ -393,7 +393,7 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_fused_pairs(PathArgs a) {
   // bound by the vector ALUs: the transform with lane bits 2..5 turned into register bits (rht_tile.hpp)
   __shared__ float tbuf[TR_FLOATS];
   __shared__ float xbuf[TX_FLOATS];
-  const int wave = wave_id(), lane = lane_id(), kt = Geo<K>::KT;
+  const int wave = wave_id(), lane = lane_id();
   const u64 L = a.n_pad, nblocks = L >> K;
   // workgroup -> (block, h); the HP workgroups of a block sit on one XCD, next to each other
   u64 blk;
