@@ -249,7 +249,8 @@ or_status check_transform(const void* in, u64 in_len, int in_es, void* out, u64 
   if (!aligned(in, 16) || !aligned(out, 16)) return OR_ERR_ALIGN;
   if (in_len > ((u64)1 << 46) || out_len > ((u64)1 << 46)) return OR_ERR_SHAPE;
   if (ranges_overlap(in, in_len * in_es, out, out_len * out_es)) {
-    const bool exact_in_place = (in == out) && in_len == out_len && in_es == out_es && k <= 14;
+    // every workgroup reads the whole of its tile (or block of tiles) before it writes any of it
+    const bool exact_in_place = (in == out) && in_len == out_len && in_es == out_es;
     if (!exact_in_place) return OR_ERR_SHAPE;
   }
   return OR_OK;
