@@ -29,13 +29,6 @@ typedef Geo<K> G;
     return launch_kernel(kernel, dim3((unsigned)blocks), dim3(G::THREADS), s, pos, a);       \
   }
 
-#define OR_BATCH_LAUNCHER(name, kernel)                                                       \
-  hipError_t name(const BatchArgs& a, unsigned long long units, hipStream_t s, int pos) {   \
-    if (units == 0) return hipSuccess;                                                       \
-    if (units > 0x7FFFFFFFull) return hipErrorInvalidValue;                                  \
-    return launch_kernel(kernel, dim3((unsigned)units), dim3(G::THREADS), s, pos, a);        \
-  }
-
 #define OR_SPLIT_LAUNCHER(name, LAUNCHER, kernel_full, kernel_tail)                          \
   LAUNCHER(name##_full, kernel_full)                                                         \
   LAUNCHER(name##_tail, kernel_tail)                                                         \
@@ -74,10 +67,28 @@ OR_SPLIT_LAUNCHER(mdec_bf16, OR_XFORM_LAUNCHER, OR_DEC(bf16_t, false, true, true
 #if OR_K <= 14
 OR_LAUNCHER(rdec_f32, (k_reduce_decode<K, float, float>))
 OR_LAUNCHER(rdec_bf16, (k_reduce_decode<K, bf16_t, bf16_t>))
-OR_LAUNCHER(fus_f32, (k_fused<K, float>))
-OR_LAUNCHER(fus_bf16, (k_fused<K, bf16_t>))
-OR_BATCH_LAUNCHER(fusb_f32, (k_fused_batched<K, float>))
-OR_BATCH_LAUNCHER(fusb_bf16, (k_fused_batched<K, bf16_t>))
+// The fused kernels come in two forms where a lane holds 16 entries: with a second tile buffer (the next
+// worker's tile travels while this one is transformed), which shortens the chain of dependent steps of a
+// workgroup and wins while a launch puts at most three workgroups on each of the 256 CUs, and without,
+// which wins beyond that (measured on MI355X; same arithmetic, same results).
+constexpr unsigned long long kPrefetchUpTo = 3 * 256;
+constexpr bool kTwoForms = (G::R == 16);
+#define OR_FUSED_LAUNCHER(name, Args, kernel)                                                \
+  hipError_t name(const Args& a, unsigned long long units, hipStream_t s, int pos) {        \
+    if (units == 0) return hipSuccess;                                                       \
+    if (units > 0x7FFFFFFFull) return hipErrorInvalidValue;                                  \
+    if (kTwoForms && units <= kPrefetchUpTo)                                                 \
+      return launch_kernel(kernel<K, OR_FUSED_IN, kTwoForms>, dim3((unsigned)units), dim3(G::THREADS), s, pos, a); \
+    return launch_kernel(kernel<K, OR_FUSED_IN, false>, dim3((unsigned)units), dim3(G::THREADS), s, pos, a); \
+  }
+#define OR_FUSED_IN float
+OR_FUSED_LAUNCHER(fus_f32, PathArgs, k_fused)
+OR_FUSED_LAUNCHER(fusb_f32, BatchArgs, k_fused_batched)
+#undef OR_FUSED_IN
+#define OR_FUSED_IN bf16_t
+OR_FUSED_LAUNCHER(fus_bf16, PathArgs, k_fused)
+OR_FUSED_LAUNCHER(fusb_bf16, BatchArgs, k_fused_batched)
+#undef OR_FUSED_IN
 #else
 // one workgroup per pair of output tiles; `units` = output tiles of the shard
 #define OR_PAIR_LAUNCHER(name, kernel)                                                       \

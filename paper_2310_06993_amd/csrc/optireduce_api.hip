@@ -39,6 +39,9 @@ thread_local int g_last_hip_error = 0;
 // ------------------------------------------------------------------ streaming masked sum + count
 // Sec. 3.1.1 aggregation with no transform around it: each lane owns VEC consecutive entries (16
 // bytes of one worker's shard), reads the VEC mask bits of every worker and adds under select.
+#ifndef OR_NT_REDUCE
+#define OR_NT_REDUCE true
+#endif
 template <class Wire, int VEC>
 __global__ __launch_bounds__(256) void k_masked_reduce(const Wire* __restrict__ shards,
                                                        const uint32_t* __restrict__ masks, int N, u64 L,
@@ -58,7 +61,8 @@ __global__ __launch_bounds__(256) void k_masked_reduce(const Wire* __restrict__ 
     uint32_t m[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      x[u] = *(const vec_t*)(shards + (u64)(i + u) * L + e);
+      x[u] = OR_NT_REDUCE ? __builtin_nontemporal_load((const vec_t*)(shards + (u64)(i + u) * L + e))
+                          : *(const vec_t*)(shards + (u64)(i + u) * L + e);
       m[u] = masks[(u64)(i + u) * words + (e >> 5)] >> sh;
     }
 #pragma unroll
@@ -73,7 +77,8 @@ __global__ __launch_bounds__(256) void k_masked_reduce(const Wire* __restrict__ 
       }
   }
   for (; i < N; ++i) {
-    vec_t x = *(const vec_t*)(shards + (u64)i * L + e);
+    vec_t x = OR_NT_REDUCE ? __builtin_nontemporal_load((const vec_t*)(shards + (u64)i * L + e))
+                           : *(const vec_t*)(shards + (u64)i * L + e);
     uint32_t m = masks[(u64)i * words + (e >> 5)] >> sh;
 #pragma unroll
     for (int j = 0; j < VEC; ++j) {

@@ -3,6 +3,30 @@
 #pragma once
 #include "rht_tile.hpp"
 
+// Which kernels read their inputs with nontemporal loads (each choice measured on MI355X; ENCB / DECB
+// are the encode / decode kernels for blocks above 2^14 entries, which came out slower with them).
+#ifndef OR_NT_FUSED
+#define OR_NT_FUSED true
+#endif
+#ifndef OR_NT_RDEC
+#define OR_NT_RDEC true
+#endif
+#ifndef OR_NT_PAIRS
+#define OR_NT_PAIRS true
+#endif
+#ifndef OR_NT_ENC
+#define OR_NT_ENC true
+#endif
+#ifndef OR_NT_ENCB
+#define OR_NT_ENCB false
+#endif
+#ifndef OR_NT_DECB
+#define OR_NT_DECB false
+#endif
+#ifndef OR_NT_DEC
+#define OR_NT_DEC true
+#endif
+
 namespace ordev {
 
 struct PathArgs {
@@ -91,7 +115,7 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_encode(PathArgs a) {
   const int wave = wave_id(), lane = lane_id(), kt = tile_bits<K>(a.k);
   const u64 unit = a.unit0 + blockIdx.x;
   float v[R];
-  load_tile<K, false, FULL>((const In*)a.in, unit * T, a.n, wave, lane, v);
+  load_tile<K, false, FULL, OR_NT_ENC>((const In*)a.in, unit * T, a.n, wave, lane, v);
   u64 sg[R];
   sign_masks(a.seed, a.base + unit * T + (u64)wave * Geo<K>::WAVE_ENTRIES, sg);
   apply_signs(v, sg);
@@ -114,7 +138,7 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_encode_block(PathArgs a) {
   const u64 tile0 = a.unit0 + ((u64)blockIdx.x << HB);
   float v[PARTS][R];
 #pragma unroll
-  for (int q = 0; q < PARTS; ++q) load_tile<K, false, FULL>((const In*)a.in, (tile0 + q) * T, a.n, wave, lane, v[q]);
+  for (int q = 0; q < PARTS; ++q) load_tile<K, false, FULL, OR_NT_ENCB>((const In*)a.in, (tile0 + q) * T, a.n, wave, lane, v[q]);
   uint32_t slo, shi;
   block_sign_words<K>(a.seed, a.base + tile0 * T + (u64)wave * Geo<K>::WAVE_ENTRIES, slo, shi);
 #pragma unroll
@@ -138,10 +162,11 @@ template <int K, bool FINALIZE, bool FULL, bool MASKED>
 __device__ __forceinline__ void load_mean_tile(const PathArgs& a, u64 tile, int wave, int lane,
                                                float (&v)[Geo<K>::R]) {
   constexpr int T = Geo<K>::T, R = Geo<K>::R;
-  load_tile<K, true, FULL>((const float*)a.in, tile * T, a.n_pad, wave, lane, v);
+  constexpr bool NT = Geo<K>::PARTS == 1 ? OR_NT_DEC : OR_NT_DECB;
+  load_tile<K, true, FULL, NT>((const float*)a.in, tile * T, a.n_pad, wave, lane, v);
   if constexpr (FINALIZE) {
     float c[R];
-    load_tile<K, true, FULL>(a.count_in, tile * T, a.n_pad, wave, lane, c);
+    load_tile<K, true, FULL, NT>(a.count_in, tile * T, a.n_pad, wave, lane, c);
 #pragma unroll
     for (int r = 0; r < R; ++r) v[r] = c[r] > 0.0f ? v[r] * __builtin_amdgcn_rcpf(c[r]) : 0.0f;   // as finalize_mean
   }
@@ -277,17 +302,17 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_reduce_decode(PathArgs a) {
   for (int r = 0; r < R; ++r) acc[r] = 0.0f;
 #pragma unroll
   for (int r = 0; r < R / 4; ++r) cnt[r] = 0;
-  load_tile<K, true, FULL>(shards, e0, L, wave, lane, va);
+  load_tile<K, true, FULL, OR_NT_RDEC>(shards, e0, L, wave, lane, va);
   ma = load_mask_words<K, FULL>(a.masks, e0, L, moff);
   for (int i = 0; i < a.N; i += 2) {
     if (i + 1 < a.N) {
-      load_tile<K, true, FULL>(shards + (u64)(i + 1) * L, e0, L, wave, lane, vb);
+      load_tile<K, true, FULL, OR_NT_RDEC>(shards + (u64)(i + 1) * L, e0, L, wave, lane, vb);
       mb = load_mask_words<K, FULL>(a.masks + (u64)(i + 1) * mrow, e0, L, moff);
     }
     masked_accumulate(va, ma, acc, cnt, full);
     if (i + 1 < a.N) {
       if (i + 2 < a.N) {
-        load_tile<K, true, FULL>(shards + (u64)(i + 2) * L, e0, L, wave, lane, va);
+        load_tile<K, true, FULL, OR_NT_RDEC>(shards + (u64)(i + 2) * L, e0, L, wave, lane, va);
         ma = load_mask_words<K, FULL>(a.masks + (u64)(i + 2) * mrow, e0, L, moff);
       }
       masked_accumulate(vb, mb, acc, cnt, full);
@@ -311,18 +336,22 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_reduce_decode(PathArgs a) {
 // three separate calls give.  Blocks of up to 2^14 entries (one tile per block).
 //
 // Per worker: sign flip (layout A), transform to layout B, round, add under the received mask.
-// No register prefetch of the next worker's tile: measured on MI355X, keeping the kernel small enough
-// for several independent workgroups per CU hides the load latency better than a second tile buffer.
-template <int K, class In>
+// PREFETCH: a second tile buffer, so that the next worker's tile is in flight during the transform (the
+// launcher decides from the size of the grid).  Inputs are read once: nontemporal loads.
+template <int K, class In, bool PREFETCH>
 __device__ __forceinline__ void fused_tile(const PathArgs& a, u64 unit) {
   constexpr int T = Geo<K>::T, NB = kXbufs<K>, R = Geo<K>::R;
   constexpr bool FULL = kShardTilesFull<K>;
+  static_assert(!PREFETCH || R == 16, "a second tile buffer only with 16 entries per lane");
   static_assert(Geo<K>::PARTS == 1, "larger blocks use k_fused_pairs");
-  __shared__ float xbuf[NB ? NB : 1][NB ? T : 1];
+  constexpr bool TRANSP = (R == 16 && Geo<K>::W == 4);    // encode by transform_transposed4
+  constexpr int XF = TRANSP ? T4_FLOATS : T;
+  __shared__ float xbuf[NB ? NB : 1][NB ? XF : 1];
   const int wave = wave_id(), lane = lane_id(), kt = tile_bits<K>(a.k);
   const u64 L = a.n_pad, e0 = unit * T;
   const In* grads = (const In*)a.in;
-  const float sigma = lane_sigma(lane, kt < 6 ? kt : 6);
+  const float sigma_dec = lane_sigma(lane, kt < 6 ? kt : 6);
+  const float sigma = TRANSP ? tr_sigma(lane) : sigma_dec;
   // a power-of-two scale commutes with rounding to the wire type; any other scale is applied first
   const bool scale_first = sizeof(In) == 2 && (a.k & 1);
   float acc[R], va[R];
@@ -331,7 +360,7 @@ __device__ __forceinline__ void fused_tile(const PathArgs& a, u64 unit) {
   const int moff = mask_word_offset<K>(wave, lane);
   const u64 mrow = L >> 5;
   // the first worker's tile is requested before the signs are computed, so Philox runs under its latency
-  load_tile<K, false, FULL>(grads, e0, L, wave, lane, va);
+  load_tile<K, false, FULL, OR_NT_FUSED>(grads, e0, L, wave, lane, va);
   uint32_t ma = load_mask_words<K, FULL>(a.masks, e0, L, moff);
   u64 sg[R];
   sign_masks(a.seed, a.base + e0 + (u64)wave * Geo<K>::WAVE_ENTRIES, sg);
@@ -340,42 +369,78 @@ __device__ __forceinline__ void fused_tile(const PathArgs& a, u64 unit) {
 #pragma unroll
   for (int r = 0; r < R / 4; ++r) cnt[r] = 0;
 
-  for (int i = 0; i < a.N; ++i) {
-    apply_signs(va, sg);
-    transform<K, true, NB != 2>(va, xbuf[NB == 2 ? flip : 0], wave, lane, kt);
+  auto encode_and_add = [&](float (&v)[R], uint32_t words) {
+    apply_signs(v, sg);
+    if constexpr (TRANSP) {
+      static_assert(NB == 2, "two buffers");
+      transform_transposed4<K>(v, xbuf[flip], xbuf[flip ^ 1], wave, lane);
+    } else {
+      transform<K, true, NB != 2>(v, xbuf[NB == 2 ? flip : 0], wave, lane, kt);
+    }
     flip ^= 1;
     if (sizeof(In) == 2) {
       if (scale_first) {
 #pragma unroll
-        for (int r = 0; r < R; ++r) va[r] = round_to<In>(va[r] * a.scale);
+        for (int r = 0; r < R; ++r) v[r] = round_to<In>(v[r] * a.scale);
       } else {
 #pragma unroll
-        for (int r = 0; r < R; ++r) va[r] = round_to<In>(va[r]);
+        for (int r = 0; r < R; ++r) v[r] = round_to<In>(v[r]);
       }
     }
-    masked_accumulate(va, ma, acc, cnt, full);
+    masked_accumulate(v, words, acc, cnt, full);
+  };
+  if constexpr (PREFETCH) {
+    // Two tile buffers: the next worker's tile travels while this one is transformed.  The loads inside
+    // the loop are unconditional (the last one or two workers are handled after it), so that the count
+    // of loads in flight is the same on every path into a wait and the compiler waits for the older
+    // tile only.
+    float vb[R];
+    uint32_t mb;
+    auto request = [&](int i, float (&v)[R], uint32_t& words) {
+      load_tile<K, false, FULL, OR_NT_FUSED>(grads + (u64)i * L, e0, L, wave, lane, v);
+      words = load_mask_words<K, FULL>(a.masks + (u64)i * mrow, e0, L, moff);
+    };
+    int i = 0;
+    for (; i + 2 < a.N; i += 2) {
+      request(i + 1, vb, mb);
+      encode_and_add(va, ma);
+      request(i + 2, va, ma);
+      encode_and_add(vb, mb);
+    }
     if (i + 1 < a.N) {
-      load_tile<K, false, FULL>(grads + (u64)(i + 1) * L, e0, L, wave, lane, va);
-      ma = load_mask_words<K, FULL>(a.masks + (u64)(i + 1) * mrow, e0, L, moff);
+      request(i + 1, vb, mb);
+      encode_and_add(va, ma);
+      encode_and_add(vb, mb);
+    } else {
+      encode_and_add(va, ma);
+    }
+  } else {
+    for (int i = 0; i < a.N; ++i) {
+      encode_and_add(va, ma);
+      if (i + 1 < a.N) {
+        load_tile<K, false, FULL, OR_NT_FUSED>(grads + (u64)(i + 1) * L, e0, L, wave, lane, va);
+        ma = load_mask_words<K, FULL>(a.masks + (u64)(i + 1) * mrow, e0, L, moff);
+      }
     }
   }
   __builtin_amdgcn_sched_barrier(0);
   store_counts<K, FULL>(a.count_out, e0, L, wave, lane, cnt, full);
   finalize_mean(acc, cnt, full, sigma * (scale_first ? 1.0f : a.scale));
   __builtin_amdgcn_sched_barrier(0);
-  transform<K, false, NB != 2>(acc, xbuf[NB == 2 ? flip : 0], wave, lane, kt);
+  // the buffer that no wavefront can still be reading: not the one the last exchange went through
+  transform<K, false, NB != 2>(acc, xbuf[NB == 2 ? (TRANSP ? flip ^ 1 : flip) : 0], wave, lane, kt);
   __builtin_amdgcn_sched_barrier(0);
-  const float c = a.scale * sigma;
+  const float c = a.scale * sigma_dec;
 #pragma unroll
   for (int r = 0; r < R; ++r) acc[r] *= c;
   apply_signs(acc, sg);
   store_tile<K, false, FULL, true>((In*)a.out, e0, L, wave, lane, acc);
 }
 
-template <int K, class In>
+template <int K, class In, bool PREFETCH>
 __global__ __launch_bounds__(Geo<K>::THREADS) __attribute__((amdgpu_waves_per_eu(Geo<K>::R == 32 ? 4 : 1)))
 void k_fused(PathArgs a) {
-  fused_tile<K, In>(a, blockIdx.x);
+  fused_tile<K, In, PREFETCH>(a, blockIdx.x);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -457,15 +522,15 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_fused_pairs(PathArgs a) {
     const In* x = grads + (u64)i * L;
     float A[R], C[R], t[R], w[R];
     // up to three tiles in flight: u_0 -> A, u_1 -> t (four-tile blocks), u_HP -> C
-    load_tile<K, false, true>(x, t0 * T, L, wave, lane, A);
-    if constexpr (HP == 2) load_tile<K, false, true>(x, (t0 + 1) * T, L, wave, lane, t);
-    load_tile<K, false, true>(x, (t0 + HP) * T, L, wave, lane, C);
+    load_tile<K, false, true, OR_NT_PAIRS>(x, t0 * T, L, wave, lane, A);
+    if constexpr (HP == 2) load_tile<K, false, true, OR_NT_PAIRS>(x, (t0 + 1) * T, L, wave, lane, t);
+    load_tile<K, false, true, OR_NT_PAIRS>(x, (t0 + HP) * T, L, wave, lane, C);
     const uint32_t m_lo = load_mask_words<K, true>(a.masks + (u64)i * mrow, e_lo, L, moff);
     const uint32_t m_hi = load_mask_words<K, true>(a.masks + (u64)i * mrow, e_hi, L, moff);
     add_signed(A, A, 0, 1.0f, true);
     if constexpr (HP == 2) {
       add_signed(A, t, 1, part_coef(h, 1), false);
-      load_tile<K, false, true>(x, (t0 + HP + 1) * T, L, wave, lane, t);
+      load_tile<K, false, true, OR_NT_PAIRS>(x, (t0 + HP + 1) * T, L, wave, lane, t);
     }
     add_signed(C, C, HP, 1.0f, true);
     if constexpr (HP == 2) add_signed(C, t, HP + 1, part_coef(h, 1), false);
@@ -507,7 +572,7 @@ struct BatchArgs {
 
 static_assert(sizeof(BatchArgs) <= 4096, "kernel arguments are limited to 4 KB");
 
-template <int K, class In>
+template <int K, class In, bool PREFETCH>
 __global__ __launch_bounds__(Geo<K>::THREADS) __attribute__((amdgpu_waves_per_eu(Geo<K>::R == 32 ? 4 : 1)))
 void k_fused_batched(BatchArgs ba) {
   const uint32_t x = blockIdx.x;
@@ -517,7 +582,7 @@ void k_fused_batched(BatchArgs ba) {
   a.in = ba.b[j].in; a.masks = ba.b[j].masks; a.out = ba.b[j].out; a.count_out = ba.b[j].count_out;
   a.n = a.n_pad = ba.b[j].shard_len; a.seed = ba.b[j].seed; a.base = ba.b[j].base;
   a.N = ba.N; a.k = ba.k; a.scale = ba.scale;
-  fused_tile<K, In>(a, x - ba.tile_start[j]);
+  fused_tile<K, In, PREFETCH>(a, x - ba.tile_start[j]);
 }
 
 }  // namespace ordev

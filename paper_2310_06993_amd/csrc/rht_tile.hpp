@@ -101,6 +101,15 @@ template <bool NT> __device__ __forceinline__ void store_one(uint8_t* p, uint8_t
 template <bool NT> __device__ __forceinline__ void store_one(bf16_t* p, bf16_t v) {
   if (NT) __builtin_nontemporal_store(v.bits, &p->bits); else p->bits = v.bits;
 }
+template <bool NT> __device__ __forceinline__ float load_one(const float* p) {
+  return NT ? __builtin_nontemporal_load(p) : *p;
+}
+template <bool NT> __device__ __forceinline__ uint8_t load_one(const uint8_t* p) {
+  return NT ? __builtin_nontemporal_load(p) : *p;
+}
+template <bool NT> __device__ __forceinline__ bf16_t load_one(const bf16_t* p) {
+  return bf16_t{NT ? __builtin_nontemporal_load(&p->bits) : p->bits};
+}
 template <class T> __device__ __forceinline__ float round_to(float v) { return to_f32(from_f32<T>(v)); }
 
 // ------------------------------------------------------------------ Philox4x32-10 (Salmon et al., SC'11)
@@ -332,6 +341,40 @@ __device__ __forceinline__ void transform_transposed(float (&v)[16], float* tbuf
   reg_stages(v, 0, 4);
 }
 
+// The same for tiles of 4 wavefronts x 16 registers (2^12 entries).  `ta` and `tb` are two buffers of
+// T4_FLOATS floats; the caller swaps them from one call to the next, which leaves one barrier per call:
+// the transposition is written into the wavefront's own part of `ta` (last read by this wavefront, in the
+// exchange of the call before), the exchange into `tb` (last read as the transposition buffer of the call
+// before, by its owner, ahead of that call's barrier).
+//   after step 3 wavefront w, register r', lane l' holds entry (l' & 3) | r' << 2 | (l' >> 2) << 6 | w << 10;
+//   layout B wants wavefront (l' >> 4), register ((l' >> 2) & 3) | w << 2, lane (l' & 3) | r' << 2.
+// Rows of a register are 68 floats apart and the parts of the wavefronts 1104 (= 16 mod 64), so that the
+// 64 lanes of a store land in 64 different banks; so do those of a load (bank = lane + 4 register).
+constexpr int T4_WAVE = 16 * TR_ROW + 16, T4_FLOATS = 4 * T4_WAVE;
+template <int K>
+__device__ __forceinline__ void transform_transposed4(float (&v)[16], float* ta, float* tb, int wave, int lane) {
+  static_assert(Geo<K>::R == 16 && Geo<K>::W == 4, "4 wavefronts of 16 registers");
+  reg_stages(v, 0, 4);
+  lane_stage<0>(v, lane);
+  lane_stage<1>(v, lane);
+  float* mine = ta + wave * T4_WAVE;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) mine[r * TR_ROW + lane] = v[r];
+  __builtin_amdgcn_wave_barrier();
+  const float* back = mine + (lane >> 2) * TR_ROW + (lane & 3);
+#pragma unroll
+  for (int r = 0; r < 16; ++r) v[r] = back[r * 4];
+  reg_stages(v, 0, 4);
+  float* to = tb + (lane >> 4) * T4_WAVE + (((lane >> 2) & 3) + wave * 4) * TR_ROW + (lane & 3);
+#pragma unroll
+  for (int r = 0; r < 16; ++r) to[r * 4] = v[r];
+  __syncthreads();
+  const float* from = tb + wave * T4_WAVE + lane;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) v[r] = from[r * TR_ROW];
+  reg_stages(v, 2, 4);
+}
+
 // ------------------------------------------------------------------ tile loads / stores
 // `p` points at entry 0 of the vector, `e0` is the tile's first entry, `limit` the number of valid
 // entries of the vector; entries at or beyond `limit` read as zero / are not written.  FULL = true
@@ -364,7 +407,9 @@ __device__ __forceinline__ void buf_store(__amdgpu_buffer_rsrc_t r, int entry, f
   __builtin_amdgcn_raw_buffer_store_b8(from_f32<uint8_t>(v), r, entry, 0, 0);
 }
 
-template <int K, bool LAYOUT_B, bool FULL, class T>
+// NT = true: nontemporal loads, for inputs that are read once.  Measured on MI355X: 4-7 % faster for the
+// N-to-1 shard kernels.
+template <int K, bool LAYOUT_B, bool FULL, bool NT = false, class T>
 __device__ __forceinline__ void load_tile(const T* __restrict__ p, u64 e0, u64 limit, int wave, int lane,
                                           float (&v)[Geo<K>::R]) {
   constexpr int R = Geo<K>::R;
@@ -373,7 +418,8 @@ __device__ __forceinline__ void load_tile(const T* __restrict__ p, u64 e0, u64 l
     const T* q = p + e0;
     const unsigned l = (unsigned)lane;
 #pragma unroll
-    for (int r = 0; r < R; ++r) v[r] = to_f32((q + (LAYOUT_B ? off_b<K>(wave, r) : off_a<K>(wave, r)))[l]);
+    for (int r = 0; r < R; ++r)
+      v[r] = to_f32(load_one<NT>(&(q + (LAYOUT_B ? off_b<K>(wave, r) : off_a<K>(wave, r)))[l]));
   } else {
     const __amdgpu_buffer_rsrc_t rs = tile_rsrc(p, e0, limit);
 #pragma unroll
