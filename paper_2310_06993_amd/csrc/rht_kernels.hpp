@@ -456,8 +456,8 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_fused_pairs(PathArgs a) {
   constexpr int T = Geo<K>::T, R = Geo<K>::R, HB = Geo<K>::HB, PARTS = Geo<K>::PARTS, HP = PARTS / 2;
   static_assert(PARTS == 2 || PARTS == 4, "two or four tiles per block");
   // bound by the vector ALUs: the transform with lane bits 2..5 turned into register bits (rht_tile.hpp)
-  __shared__ float tbuf[TR_FLOATS];
-  __shared__ float xbuf[TX_FLOATS];
+  __shared__ float tbuf[2][TR_FLOATS];   // alternate between the two roles: one barrier per transform
+  int flip = 0;
   const int wave = wave_id(), lane = lane_id();
   const u64 L = a.n_pad, nblocks = L >> K;
   // workgroup -> (block, h); the HP workgroups of a block sit on one XCD, next to each other
@@ -505,7 +505,8 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_fused_pairs(PathArgs a) {
     __builtin_amdgcn_sched_barrier(0);
   };
   auto finish_tile = [&](float (&v)[R], uint32_t m, float (&acc)[R], uint32_t (&cnt)[R / 4], int& full) {
-    transform_transposed<K>(v, tbuf, xbuf, wave, lane);
+    transform_transposed<K>(v, tbuf[flip], tbuf[flip ^ 1], wave, lane);
+    flip ^= 1;
     if (sizeof(In) == 2) {
       if (scale_first) {
 #pragma unroll

@@ -310,42 +310,41 @@ __device__ __forceinline__ void transform(float (&v)[Geo<K>::R], float* xbuf, in
 //   3. register stages (entry bits 2..5)
 //   4. exchange between wavefronts, written straight to layout-B positions: the value in wavefront w,
 //      register r', lane l' is entry (l' & 3) | (r' << 2) | ((l' >> 2) << 6) | (w << 10) of the tile;
-//      rows of a receiving wavefront are 1028 floats apart for the same reason as above
+//      the parts of the receiving wavefronts are 1092 floats apart for the same reason as above
 //   5. register stages (entry bits 10..13)
-constexpr int TR_ROW = 68, TR_WAVE = 16 * TR_ROW, TR_FLOATS = 16 * TR_WAVE;   // transposition buffer
-constexpr int TX_WAVE = 16 * 64 + 4, TX_FLOATS = 16 * TX_WAVE;                // exchange buffer
+// `ta` and `tb` are two buffers of TR_FLOATS floats; the caller swaps them from one call to the next, which
+// leaves one barrier per call: the transposition is written into the wavefront's own part of `ta` (last
+// read by this wavefront, in the exchange of the call before), the exchange into `tb` (last read as the
+// transposition buffer of the call before, by its owner, ahead of that call's barrier).
+constexpr int TR_ROW = 68;                                       // floats per register row of a transposition
+constexpr int TR_WAVE = 16 * TR_ROW + 4, TR_FLOATS = 16 * TR_WAVE;   // part of a wavefront: 1092 = 4 mod 64
 __device__ __forceinline__ float tr_sigma(int lane) { return (__builtin_popcount(lane & 3) & 1) ? -1.0f : 1.0f; }
 
 template <int K>
-__device__ __forceinline__ void transform_transposed(float (&v)[16], float* tbuf, float* xbuf, int wave, int lane) {
+__device__ __forceinline__ void transform_transposed(float (&v)[16], float* ta, float* tb, int wave, int lane) {
   static_assert(Geo<K>::R == 16 && Geo<K>::W == 16, "16 wavefronts of 16 registers");
   reg_stages(v, 0, 4);
   lane_stage<0>(v, lane);
   lane_stage<1>(v, lane);
-  float* mine = tbuf + wave * TR_WAVE;
+  float* mine = ta + wave * TR_WAVE;
 #pragma unroll
   for (int r = 0; r < 16; ++r) mine[r * TR_ROW + lane] = v[r];
-  __builtin_amdgcn_wave_barrier();   // lanes read what other lanes of this wavefront wrote: keep the order
+  __builtin_amdgcn_wave_barrier();
   const float* back = mine + (lane >> 2) * TR_ROW + (lane & 3);
 #pragma unroll
   for (int r = 0; r < 16; ++r) v[r] = back[r * 4];
   reg_stages(v, 0, 4);
-  __syncthreads();   // the exchange buffer may still be read from the previous exchange
-  float* to = xbuf + (lane >> 2) * TX_WAVE + wave * 64 + (lane & 3);
+  float* to = tb + (lane >> 2) * TR_WAVE + wave * 64 + (lane & 3);
 #pragma unroll
   for (int r = 0; r < 16; ++r) to[r * 4] = v[r];
   __syncthreads();
-  const float* from = xbuf + wave * TX_WAVE + lane;
+  const float* from = tb + wave * TR_WAVE + lane;
 #pragma unroll
   for (int r = 0; r < 16; ++r) v[r] = from[r * 64];
   reg_stages(v, 0, 4);
 }
 
-// The same for tiles of 4 wavefronts x 16 registers (2^12 entries).  `ta` and `tb` are two buffers of
-// T4_FLOATS floats; the caller swaps them from one call to the next, which leaves one barrier per call:
-// the transposition is written into the wavefront's own part of `ta` (last read by this wavefront, in the
-// exchange of the call before), the exchange into `tb` (last read as the transposition buffer of the call
-// before, by its owner, ahead of that call's barrier).
+// The same for tiles of 4 wavefronts x 16 registers (2^12 entries), two buffers of T4_FLOATS floats.
 //   after step 3 wavefront w, register r', lane l' holds entry (l' & 3) | r' << 2 | (l' >> 2) << 6 | w << 10;
 //   layout B wants wavefront (l' >> 4), register ((l' >> 2) & 3) | w << 2, lane (l' & 3) | r' << 2.
 // Rows of a register are 68 floats apart and the parts of the wavefronts 1104 (= 16 mod 64), so that the
