@@ -483,3 +483,44 @@ def test_two_level_reduce(b, orc, G, M, L):
     # the same as one level with a lost group = all its members lost (counts exactly, sums to rounding)
     w1, c1 = orc.masked_reduce(x, pack_mask_np(recv & np.repeat(recv2, M, axis=0)))
     assert np.array_equal(to_np(count), c1) and rel_l2(to_np(total), w1) <= TOL["f32"]
+
+
+@pytest.mark.parametrize("k,kind", [(8, "f32"), (11, "f32"), (12, "f32"), (12, "bf16")])
+def test_fused_forms_on_both_sides_of_the_grid_size_switch(b, orc, k, kind):
+    """Launches of up to 768 tiles use the kernel form that prefetches the next worker's tile, larger ones
+    the plain form: same arithmetic, so a shard of 769 tiles must reproduce, bit for bit, what its first 768
+    tiles give as a shard of their own; sampled blocks of the large launch are checked against the oracle."""
+    N = 3
+    tile = max(1 << k, 1024)
+    L_small, L_big = 768 * tile, 769 * tile
+    g = torch.Generator(device=dev()).manual_seed(40 + k)
+    raw = torch.randn((N, L_big), generator=g, device=dev()) * 1e-3
+    recv = torch.rand((N, L_big), generator=g, device=dev()) > 0.02
+    recv[0] = True
+    words = recv.view(N, L_big // 32, 32).to(torch.int64)
+    masks = (words << torch.arange(32, device=dev(), dtype=torch.int64)).sum(dim=2)
+    masks = torch.where(masks >= 2 ** 31, masks - 2 ** 32, masks).to(torch.int32).contiguous()
+    if kind == "bf16":
+        raw = raw.to(torch.bfloat16)
+    seed, base = 77 + k, 0
+    fused = b.or_fused_path if kind == "f32" else b.or_fused_path_bf16
+    out_big = torch.empty(L_big, dtype=raw.dtype, device=dev())
+    cnt_big = torch.empty(L_big, dtype=torch.uint8, device=dev())
+    fused(raw, masks, N, L_big, k, seed, base, out_big, cnt_big, _workspace(b, L_big, k))
+    raw_s = raw[:, :L_small].contiguous()
+    masks_s = masks[:, : L_small // 32].contiguous()
+    out_s = torch.empty(L_small, dtype=raw.dtype, device=dev())
+    cnt_s = torch.empty(L_small, dtype=torch.uint8, device=dev())
+    fused(raw_s, masks_s, N, L_small, k, seed, base, out_s, cnt_s, _workspace(b, L_small, k))
+    torch.cuda.synchronize()
+    assert torch.equal(out_big[:L_small].view(torch.int32 if kind == "f32" else torch.int16),
+                       out_s.view(torch.int32 if kind == "f32" else torch.int16))
+    assert torch.equal(cnt_big[:L_small], cnt_s)
+    # oracle on the first, a middle and the last tile of the large launch
+    for t in (0, 400, 768):
+        sl = slice(t * tile, (t + 1) * tile)
+        r = to_np(raw[:, sl].contiguous())
+        m = to_np(masks[:, t * tile // 32:(t + 1) * tile // 32].contiguous())
+        want, want_count = orc.fused_path(r, m, k, seed, base + t * tile)
+        assert np.array_equal(to_np(cnt_big[sl]), want_count)
+        assert rel_l2(to_np(out_big[sl]), want) <= TOL[kind], (k, kind, t)
