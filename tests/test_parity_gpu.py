@@ -231,7 +231,8 @@ def test_reduce_decode_and_fused(b, orc, k, N, blocks, kind):
         assert (to_np(out2) != want).mean() < 0.02
 
 
-@pytest.mark.parametrize("k,N,blocks", [(16, 1, 1), (15, 9, 3), (16, 2, 3), (12, 1, 2), (14, 17, 1)])
+@pytest.mark.parametrize("k,N,blocks", [(16, 1, 1), (15, 9, 3), (16, 2, 3), (12, 1, 2), (14, 17, 1), (12, 2, 1),
+                                        (12, 5, 3), (11, 4, 5), (9, 7, 11), (12, 16, 2)])
 def test_fused_worker_counts_and_64_bit_seeds(b, orc, k, N, blocks):
     """One worker, odd worker counts, a seed with high bits set, a base index beyond 2^32."""
     L = blocks << k
