@@ -350,8 +350,7 @@ __device__ __forceinline__ void fused_tile(const PathArgs& a, u64 unit) {
   const int wave = wave_id(), lane = lane_id(), kt = tile_bits<K>(a.k);
   const u64 L = a.n_pad, e0 = unit * T;
   const In* grads = (const In*)a.in;
-  const float sigma_dec = lane_sigma(lane, kt < 6 ? kt : 6);
-  const float sigma = TRANSP ? tr_sigma(lane) : sigma_dec;
+  const float sigma = TRANSP ? tr_sigma(lane) : lane_sigma(lane, kt < 6 ? kt : 6);
   // a power-of-two scale commutes with rounding to the wire type; any other scale is applied first
   const bool scale_first = sizeof(In) == 2 && (a.k & 1);
   float acc[R], va[R];
@@ -427,10 +426,14 @@ __device__ __forceinline__ void fused_tile(const PathArgs& a, u64 unit) {
   store_counts<K, FULL>(a.count_out, e0, L, wave, lane, cnt, full);
   finalize_mean(acc, cnt, full, sigma * (scale_first ? 1.0f : a.scale));
   __builtin_amdgcn_sched_barrier(0);
-  // the buffer that no wavefront can still be reading: not the one the last exchange went through
-  transform<K, false, NB != 2>(acc, xbuf[NB == 2 ? (TRANSP ? flip ^ 1 : flip) : 0], wave, lane, kt);
+  if constexpr (TRANSP) {
+    // with 4 wavefronts of 16 registers the same code takes layout B to layout A
+    transform_transposed4<K>(acc, xbuf[flip], xbuf[flip ^ 1], wave, lane);
+  } else {
+    transform<K, false, NB != 2>(acc, xbuf[NB == 2 ? flip : 0], wave, lane, kt);
+  }
   __builtin_amdgcn_sched_barrier(0);
-  const float c = a.scale * sigma_dec;
+  const float c = a.scale * sigma;
 #pragma unroll
   for (int r = 0; r < R; ++r) acc[r] *= c;
   apply_signs(acc, sg);

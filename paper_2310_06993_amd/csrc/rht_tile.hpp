@@ -344,7 +344,9 @@ __device__ __forceinline__ void transform_transposed(float (&v)[16], float* ta, 
   reg_stages(v, 0, 4);
 }
 
-// The same for tiles of 4 wavefronts x 16 registers (2^12 entries), two buffers of T4_FLOATS floats.
+// The same for tiles of 4 wavefronts x 16 registers (2^12 entries), two buffers of T4_FLOATS floats.  Layout A
+// in, layout B out -- or layout B in, layout A out: with this geometry both are the same map of (wavefront,
+// register, lane), only the entry bits that the positions stand for differ.
 //   after step 3 wavefront w, register r', lane l' holds entry (l' & 3) | r' << 2 | (l' >> 2) << 6 | w << 10;
 //   layout B wants wavefront (l' >> 4), register ((l' >> 2) & 3) | w << 2, lane (l' & 3) | r' << 2.
 // Rows of a register are 68 floats apart and the parts of the wavefronts 1104 (= 16 mod 64), so that the
