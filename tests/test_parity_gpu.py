@@ -351,12 +351,13 @@ def test_errors_leave_outputs_untouched(b):
     assert bool((out == 7.0).all())
 
 
-@pytest.mark.parametrize("k,kind", [(12, "f32"), (10, "bf16"), (16, "f32")])
-def test_batched_buckets_equal_single_calls(b, orc, k, kind):
+@pytest.mark.parametrize("k,kind,long", [(12, "f32", 0), (10, "bf16", 0), (16, "f32", 0), (12, "f32", 20), (11, "bf16", 14)])
+def test_batched_buckets_equal_single_calls(b, orc, k, kind, long):
     # buckets of different lengths in one call (more than 64 of them for k = 12: several launches)
     B = 1 << k
     N = 4
-    lens = [B * (1 + j % 3) for j in range(70)] if k == 12 else [2 * B, B, 0, 3 * B]
+    # long: launches of more than 768 tiles, which take the other form of the kernel
+    lens = [B * (long + 1 + j % 3) for j in range(70)] if k == 12 or long else [2 * B, B, 0, 3 * B]
     dt = torch.float32 if kind == "f32" else torch.bfloat16
     gen = torch.Generator(device=dev()).manual_seed(k)
     items, singles = [], []
