@@ -526,3 +526,55 @@ def test_fused_forms_on_both_sides_of_the_grid_size_switch(b, orc, k, kind):
         want, want_count = orc.fused_path(r, m, k, seed, base + t * tile)
         assert np.array_equal(to_np(cnt_big[sl]), want_count)
         assert rel_l2(to_np(out_big[sl]), want) <= TOL[kind], (k, kind, t)
+
+
+def test_seeded_sweep_of_shapes_through_every_route(b, orc):
+    """Twenty seeded draws of (block size, workers, blocks, type, loss rate): the fused path, reduce+decode
+    on the library's own encode output, and encode -> masked reduce -> finalize+decode must all land on the
+    oracle, with identical counts."""
+    rng = np.random.default_rng(20231006)
+    for case in range(20):
+        k = int(rng.integers(5, 17))
+        N = int(rng.integers(1, 12))
+        blocks = int(rng.integers(1, 5)) if k >= 13 else int(rng.integers(1, 40))
+        kind = "f32" if rng.random() < 0.6 else "bf16"
+        loss = float(rng.choice([0.0, 0.01, 0.2]))
+        L = blocks << k
+        raw32 = (rng.standard_normal((N, L)) * 1e-3).astype(np.float32)
+        recv = rng.random((N, L)) >= loss
+        recv[case % N] = True
+        masks = pack_mask_np(recv)
+        md = masks_to_dev(masks)
+        seed, base = int(rng.integers(1, 2 ** 62)), int(rng.integers(0, 1000)) * max(1 << k, 128)
+        tag = (case, k, N, blocks, kind, loss)
+        ws = _workspace(b, L, k)
+        cnt_f = torch.empty(L, dtype=torch.uint8, device=dev())
+        cnt_r = torch.empty(L, dtype=torch.uint8, device=dev())
+        cnt_3 = torch.empty(L, dtype=torch.uint8, device=dev())
+        tot = torch.empty(L, device=dev())
+        if kind == "f32":
+            raw = raw32
+            gd = torch.from_numpy(raw).to(dev())
+            out_f, out_r, out_3 = (torch.empty(L, device=dev()) for _ in range(3))
+            enc = torch.empty((N, L), device=dev())
+            b.or_fused_path(gd, md, N, L, k, seed, base, out_f, cnt_f, ws)
+            for i in range(N):
+                b.or_rht_encode_at(gd[i], L, k, seed, base, enc[i])
+            b.or_reduce_decode(enc, md, N, L, k, seed, base, out_r, cnt_r, ws)
+            b.or_masked_reduce(enc, md, N, L, tot, cnt_3)
+            b.or_finalize_decode(tot, cnt_3, L, k, seed, base, out_3)
+        else:
+            raw = _bf16_bits(raw32)
+            gd = _dev_bf16(raw)
+            out_f, out_r, out_3 = (torch.empty(L, dtype=torch.bfloat16, device=dev()) for _ in range(3))
+            enc = torch.empty((N, L), dtype=torch.bfloat16, device=dev())
+            b.or_fused_path_bf16(gd, md, N, L, k, seed, base, out_f, cnt_f, ws)
+            for i in range(N):
+                b.or_rht_encode_bf16(gd[i], L, k, seed, base, enc[i])
+            b.or_reduce_decode_bf16(enc, md, N, L, k, seed, base, out_r, cnt_r, ws)
+            b.or_masked_reduce_bf16(enc, md, N, L, tot, cnt_3)
+            b.or_finalize_decode_bf16(tot, cnt_3, L, k, seed, base, out_3)
+        want, want_count = orc.fused_path(raw, masks, k, seed, base)
+        for name, out, cnt in (("fused", out_f, cnt_f), ("reduce_decode", out_r, cnt_r), ("three calls", out_3, cnt_3)):
+            assert np.array_equal(to_np(cnt), want_count), (tag, name)
+            assert rel_l2(to_np(out), want) <= TOL[kind], (tag, name)
