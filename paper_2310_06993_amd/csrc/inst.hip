@@ -12,13 +12,14 @@ namespace {
 constexpr int K = OR_K;
 typedef Geo<K> G;
 
-#define OR_LAUNCHER(name, kernel)                                                            \
+#define OR_LAUNCHER_T(name, kernel, threads)                                                 \
   /* serves output tiles a.unit0 .. a.unit0 + units - 1, one workgroup per tile */          \
   hipError_t name(const PathArgs& a, unsigned long long units, hipStream_t s, int pos) {    \
     if (units == 0) return hipSuccess;                                                       \
     if (units > 0x7FFFFFFFull) return hipErrorInvalidValue;                                  \
-    return launch_kernel(kernel, dim3((unsigned)units), dim3(G::THREADS), s, pos, a);        \
+    return launch_kernel(kernel, dim3((unsigned)units), dim3(threads), s, pos, a);           \
   }
+#define OR_LAUNCHER(name, kernel) OR_LAUNCHER_T(name, kernel, G::THREADS)
 
 // blocks above 2^14: one workgroup per block of G::PARTS tiles; a.unit0 and units count tiles
 #define OR_BLOCK_LAUNCHER(name, kernel)                                                      \
@@ -65,13 +66,16 @@ OR_SPLIT_LAUNCHER(fdec_bf16, OR_XFORM_LAUNCHER, OR_DEC(bf16_t, true, true, false
 OR_SPLIT_LAUNCHER(mdec_f32, OR_XFORM_LAUNCHER, OR_DEC(float, false, true, true), OR_DEC(float, false, false, true))
 OR_SPLIT_LAUNCHER(mdec_bf16, OR_XFORM_LAUNCHER, OR_DEC(bf16_t, false, true, true), OR_DEC(bf16_t, false, false, true))
 #if OR_K <= 14
-OR_LAUNCHER(rdec_f32, (k_reduce_decode<K, float, float>))
-OR_LAUNCHER(rdec_bf16, (k_reduce_decode<K, bf16_t, bf16_t>))
+// reduce+decode of 2^14 blocks keeps 32 entries per lane (two 8-wavefront workgroups per CU)
+constexpr int KR = (K == 14) ? K + kWide : K;
+OR_LAUNCHER_T(rdec_f32, (k_reduce_decode<KR, float, float>), Geo<KR>::THREADS)
+OR_LAUNCHER_T(rdec_bf16, (k_reduce_decode<KR, bf16_t, bf16_t>), Geo<KR>::THREADS)
 // The fused kernels come in two forms where a lane holds 16 entries: with a second tile buffer (the next
 // worker's tile travels while this one is transformed), which shortens the chain of dependent steps of a
 // workgroup and wins while a launch puts at most three workgroups on each of the 256 CUs, and without,
 // which wins beyond that (measured on MI355X; same arithmetic, same results).
-constexpr unsigned long long kPrefetchUpTo = 3 * 256;
+// (16-wavefront tiles: one workgroup per CU whatever the grid, so always the first form.)
+constexpr unsigned long long kPrefetchUpTo = (G::W == 16) ? ~0ull : 3 * 256;
 constexpr bool kTwoForms = (G::R == 16);
 #define OR_FUSED_LAUNCHER(name, Args, kernel)                                                \
   hipError_t name(const Args& a, unsigned long long units, hipStream_t s, int pos) {        \

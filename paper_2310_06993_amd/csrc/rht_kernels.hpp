@@ -335,7 +335,8 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_reduce_decode(PathArgs a) {
 // rounded to the wire type (identity for fp32) before it is summed, so the result is the one the
 // three separate calls give.  Blocks of up to 2^14 entries (one tile per block).
 //
-// Per worker: sign flip (layout A), transform to layout B, round, add under the received mask.
+// Per worker: sign flip (layout A), transform to layout B, round, add under the received mask.  Tiles of
+// 4 or 16 wavefronts x 16 registers use the transposed transforms of rht_tile.hpp, in both directions.
 // PREFETCH: a second tile buffer, so that the next worker's tile is in flight during the transform (the
 // launcher decides from the size of the grid).  Inputs are read once: nontemporal loads.
 template <int K, class In, bool PREFETCH>
@@ -345,12 +346,14 @@ __device__ __forceinline__ void fused_tile(const PathArgs& a, u64 unit) {
   static_assert(!PREFETCH || R == 16, "a second tile buffer only with 16 entries per lane");
   static_assert(Geo<K>::PARTS == 1, "larger blocks use k_fused_pairs");
   constexpr bool TRANSP = (R == 16 && Geo<K>::W == 4);    // encode by transform_transposed4
-  constexpr int XF = TRANSP ? T4_FLOATS : T;
-  __shared__ float xbuf[NB ? NB : 1][NB ? XF : 1];
+  constexpr bool TR16 = (R == 16 && Geo<K>::W == 16);     // blocks of 2^14: transform_transposed, both ways
+  constexpr int XF = TRANSP ? T4_FLOATS : TR16 ? TR_FLOATS : T;
+  constexpr int NBUF = TR16 ? 2 : NB;
+  __shared__ float xbuf[NBUF ? NBUF : 1][NBUF ? XF : 1];
   const int wave = wave_id(), lane = lane_id(), kt = tile_bits<K>(a.k);
   const u64 L = a.n_pad, e0 = unit * T;
   const In* grads = (const In*)a.in;
-  const float sigma = TRANSP ? tr_sigma(lane) : lane_sigma(lane, kt < 6 ? kt : 6);
+  const float sigma = (TRANSP || TR16) ? tr_sigma(lane) : lane_sigma(lane, kt < 6 ? kt : 6);
   // a power-of-two scale commutes with rounding to the wire type; any other scale is applied first
   const bool scale_first = sizeof(In) == 2 && (a.k & 1);
   float acc[R], va[R];
@@ -370,7 +373,9 @@ __device__ __forceinline__ void fused_tile(const PathArgs& a, u64 unit) {
 
   auto encode_and_add = [&](float (&v)[R], uint32_t words) {
     apply_signs(v, sg);
-    if constexpr (TRANSP) {
+    if constexpr (TR16) {
+      transform_transposed<K>(v, xbuf[flip], xbuf[flip ^ 1], wave, lane);
+    } else if constexpr (TRANSP) {
       static_assert(NB == 2, "two buffers");
       transform_transposed4<K>(v, xbuf[flip], xbuf[flip ^ 1], wave, lane);
     } else {
@@ -426,7 +431,9 @@ __device__ __forceinline__ void fused_tile(const PathArgs& a, u64 unit) {
   store_counts<K, FULL>(a.count_out, e0, L, wave, lane, cnt, full);
   finalize_mean(acc, cnt, full, sigma * (scale_first ? 1.0f : a.scale));
   __builtin_amdgcn_sched_barrier(0);
-  if constexpr (TRANSP) {
+  if constexpr (TR16) {
+    transform_transposed<K>(acc, xbuf[flip], xbuf[flip ^ 1], wave, lane);
+  } else if constexpr (TRANSP) {
     // with 4 wavefronts of 16 registers the same code takes layout B to layout A
     transform_transposed4<K>(acc, xbuf[flip], xbuf[flip ^ 1], wave, lane);
   } else {
