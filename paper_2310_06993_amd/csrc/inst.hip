@@ -66,16 +66,16 @@ OR_SPLIT_LAUNCHER(fdec_bf16, OR_XFORM_LAUNCHER, OR_DEC(bf16_t, true, true, false
 OR_SPLIT_LAUNCHER(mdec_f32, OR_XFORM_LAUNCHER, OR_DEC(float, false, true, true), OR_DEC(float, false, false, true))
 OR_SPLIT_LAUNCHER(mdec_bf16, OR_XFORM_LAUNCHER, OR_DEC(bf16_t, false, true, true), OR_DEC(bf16_t, false, false, true))
 #if OR_K <= 14
-// reduce+decode of 2^14 blocks keeps 32 entries per lane (two 8-wavefront workgroups per CU)
-constexpr int KR = (K == 14) ? K + kWide : K;
+// reduce+decode of 2^13 and 2^14 blocks keeps 32 entries per lane
+constexpr int KR = (K == 13 || K == 14) ? K + kWide : K;
 OR_LAUNCHER_T(rdec_f32, (k_reduce_decode<KR, float, float>), Geo<KR>::THREADS)
 OR_LAUNCHER_T(rdec_bf16, (k_reduce_decode<KR, bf16_t, bf16_t>), Geo<KR>::THREADS)
 // The fused kernels come in two forms where a lane holds 16 entries: with a second tile buffer (the next
 // worker's tile travels while this one is transformed), which shortens the chain of dependent steps of a
 // workgroup and wins while a launch puts at most three workgroups on each of the 256 CUs, and without,
 // which wins beyond that (measured on MI355X; same arithmetic, same results).
-// (16-wavefront tiles: one workgroup per CU whatever the grid, so always the first form.)
-constexpr unsigned long long kPrefetchUpTo = (G::W == 16) ? ~0ull : 3 * 256;
+// (Tiles of 8 or 16 wavefronts, at most two workgroups on a CU whatever the grid: always the first form.)
+constexpr unsigned long long kPrefetchUpTo = (G::W >= 8) ? ~0ull : 3 * 256;
 constexpr bool kTwoForms = (G::R == 16);
 #define OR_FUSED_LAUNCHER(name, Args, kernel)                                                \
   hipError_t name(const Args& a, unsigned long long units, hipStream_t s, int pos) {        \

@@ -336,7 +336,7 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_reduce_decode(PathArgs a) {
 // three separate calls give.  Blocks of up to 2^14 entries (one tile per block).
 //
 // Per worker: sign flip (layout A), transform to layout B, round, add under the received mask.  Tiles of
-// 4 or 16 wavefronts x 16 registers use the transposed transforms of rht_tile.hpp, in both directions.
+// 4, 8 or 16 wavefronts x 16 registers use the transposed transform of rht_tile.hpp, in both directions.
 // PREFETCH: a second tile buffer, so that the next worker's tile is in flight during the transform (the
 // launcher decides from the size of the grid).  Inputs are read once: nontemporal loads.
 template <int K, class In, bool PREFETCH>
@@ -345,15 +345,14 @@ __device__ __forceinline__ void fused_tile(const PathArgs& a, u64 unit) {
   constexpr bool FULL = kShardTilesFull<K>;
   static_assert(!PREFETCH || R == 16, "a second tile buffer only with 16 entries per lane");
   static_assert(Geo<K>::PARTS == 1, "larger blocks use k_fused_pairs");
-  constexpr bool TRANSP = (R == 16 && Geo<K>::W == 4);    // encode by transform_transposed4
-  constexpr bool TR16 = (R == 16 && Geo<K>::W == 16);     // blocks of 2^14: transform_transposed, both ways
-  constexpr int XF = TRANSP ? T4_FLOATS : TR16 ? TR_FLOATS : T;
-  constexpr int NBUF = TR16 ? 2 : NB;
+  constexpr bool TRANSP = (R == 16 && Geo<K>::Q >= 2);    // transform_transposed, both ways
+  constexpr int XF = TRANSP ? tr_floats<K> : T;
+  constexpr int NBUF = TRANSP ? 2 : NB;
   __shared__ float xbuf[NBUF ? NBUF : 1][NBUF ? XF : 1];
   const int wave = wave_id(), lane = lane_id(), kt = tile_bits<K>(a.k);
   const u64 L = a.n_pad, e0 = unit * T;
   const In* grads = (const In*)a.in;
-  const float sigma = (TRANSP || TR16) ? tr_sigma(lane) : lane_sigma(lane, kt < 6 ? kt : 6);
+  const float sigma = TRANSP ? tr_sigma(lane) : lane_sigma(lane, kt < 6 ? kt : 6);
   // a power-of-two scale commutes with rounding to the wire type; any other scale is applied first
   const bool scale_first = sizeof(In) == 2 && (a.k & 1);
   float acc[R], va[R];
@@ -373,11 +372,8 @@ __device__ __forceinline__ void fused_tile(const PathArgs& a, u64 unit) {
 
   auto encode_and_add = [&](float (&v)[R], uint32_t words) {
     apply_signs(v, sg);
-    if constexpr (TR16) {
+    if constexpr (TRANSP) {
       transform_transposed<K>(v, xbuf[flip], xbuf[flip ^ 1], wave, lane);
-    } else if constexpr (TRANSP) {
-      static_assert(NB == 2, "two buffers");
-      transform_transposed4<K>(v, xbuf[flip], xbuf[flip ^ 1], wave, lane);
     } else {
       transform<K, true, NB != 2>(v, xbuf[NB == 2 ? flip : 0], wave, lane, kt);
     }
@@ -431,11 +427,8 @@ __device__ __forceinline__ void fused_tile(const PathArgs& a, u64 unit) {
   store_counts<K, FULL>(a.count_out, e0, L, wave, lane, cnt, full);
   finalize_mean(acc, cnt, full, sigma * (scale_first ? 1.0f : a.scale));
   __builtin_amdgcn_sched_barrier(0);
-  if constexpr (TR16) {
-    transform_transposed<K>(acc, xbuf[flip], xbuf[flip ^ 1], wave, lane);
-  } else if constexpr (TRANSP) {
-    // with 4 wavefronts of 16 registers the same code takes layout B to layout A
-    transform_transposed4<K>(acc, xbuf[flip], xbuf[flip ^ 1], wave, lane);
+  if constexpr (TRANSP) {
+    transform_transposed<K>(acc, xbuf[flip], xbuf[flip ^ 1], wave, lane);   // the same code takes layout B to A
   } else {
     transform<K, false, NB != 2>(acc, xbuf[NB == 2 ? flip : 0], wave, lane, kt);
   }
@@ -466,7 +459,7 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_fused_pairs(PathArgs a) {
   constexpr int T = Geo<K>::T, R = Geo<K>::R, HB = Geo<K>::HB, PARTS = Geo<K>::PARTS, HP = PARTS / 2;
   static_assert(PARTS == 2 || PARTS == 4, "two or four tiles per block");
   // bound by the vector ALUs: the transform with lane bits 2..5 turned into register bits (rht_tile.hpp)
-  __shared__ float tbuf[2][TR_FLOATS];   // alternate between the two roles: one barrier per transform
+  __shared__ float tbuf[2][tr_floats<K>];   // alternate between the two roles: one barrier per transform
   int flip = 0;
   const int wave = wave_id(), lane = lane_id();
   const u64 L = a.n_pad, nblocks = L >> K;

@@ -36,10 +36,10 @@ namespace ordev {
 
 typedef unsigned long long u64;
 
-// Entries per lane: 16, except 32 for blocks of 2^13 entries and for the "wide" form of 2^14 (a 64 KB tile
-// then needs 8 wavefronts, so two workgroups fit on a CU).  Every choice was measured on MI355X against the
-// alternative: for 2^14 the encode, decode and fused kernels came out 3-5 % faster with 16 entries per lane
-// (16 wavefronts), the reduce+decode kernel 5 % faster with 32.
+// Entries per lane: 16, except 32 in the "wide" form of 2^13 and 2^14 blocks (a 64 KB tile then needs 8
+// wavefronts, so two workgroups fit on a CU).  Measured on MI355X against each other: for 2^14 the encode,
+// decode and fused kernels came out 3-5 % faster with 16 entries per lane (16 wavefronts), the reduce+decode
+// kernel 5 % faster with 32.
 constexpr int kWide = 1000;   // Geo<K + kWide>: the same block size with 32 entries per lane
 
 // Geometry for a block of 2^K entries.  KT bits are transformed inside a tile; for
@@ -50,11 +50,11 @@ template <int KSEL>
 struct Geo {
   static constexpr int K = KSEL % kWide;
   static constexpr bool WIDE = KSEL >= kWide;
-  static_assert(!WIDE || K == 14, "the wide form exists for blocks of 2^14 entries only");
+  static_assert(!WIDE || K == 13 || K == 14, "the wide form exists for blocks of 2^13 and 2^14 entries only");
   static constexpr int KT = (K == 0) ? 10 : (K > 14 ? 14 : K);
   static constexpr int TL = KT;
   static constexpr int T = 1 << TL;
-  static constexpr int RL = (K == 13 || WIDE) ? 5 : 4;
+  static constexpr int RL = WIDE ? 5 : 4;
   static constexpr int R = 1 << RL;
   static constexpr int Q = TL - 6 - RL;          // wave bits
   static_assert(Q >= 0 && Q <= 4 && Q <= RL, "unsupported tile geometry");
@@ -292,38 +292,46 @@ __device__ __forceinline__ void transform(float (&v)[Geo<K>::R], float* xbuf, in
 }
 
 // ------------------------------------------------------------------ transform with transposed lane bits
-// For tiles of 16 wavefronts x 16 registers (2^14 entries) in kernels that are bound by the vector ALUs.
+// For tiles of W = 4, 8 or 16 wavefronts x 16 registers (2^12, 2^13, 2^14 entries).
 // On MI355X a plain add/sub issues at twice the rate of anything with a DPP control, so the stages of lane
 // bits 2..5 cost three times a register stage (and those of bits 4, 5 an LDS-crossbar operation each on
 // top).  Here those four bits are made register bits by a transposition inside the wavefront (through a
 // part of LDS that belongs to the wavefront alone: no barrier) and run as register stages; only lane
-// bits 0, 1 use DPP.  Layout A in, layout B out (the same code would also take layout B to layout A:
-// with 16 wavefronts of 16 registers the exchange is the same map both ways); result on lane l times
-// tr_sigma(l).
+// bits 0, 1 use DPP.  Result on lane l times tr_sigma(l).
 //   1. register stages (entry bits 6..9), DPP stages (bits 0, 1)
 //   2. transposition: register r, lane l  ->  register (l >> 2), lane (l & 3) | (r << 2);
 //      rows of 68 floats make the write (bank 4r + l) and the read (bank 4(l' >> 2) + (l' & 3) + 4r') hit
 //      64 different banks
 //   3. register stages (entry bits 2..5)
-//   4. exchange between wavefronts, written straight to layout-B positions: the value in wavefront w,
-//      register r', lane l' is entry (l' & 3) | (r' << 2) | ((l' >> 2) << 6) | (w << 10) of the tile;
-//      the parts of the receiving wavefronts are 1092 floats apart for the same reason as above
-//   5. register stages (entry bits 10..13)
-// `ta` and `tb` are two buffers of TR_FLOATS floats; the caller swaps them from one call to the next, which
+//      now wavefront w, register r', lane l' holds entry (l' & 3) | r' << 2 | rho << 6 | w << 10 of the tile,
+//      rho = l' >> 2 the register the value sat in before step 2
+//   4. exchange between wavefronts, written straight to layout-B positions (Q = log2 W, RLO = 4 - Q):
+//      wavefront rho >> RLO, register (rho & (2^RLO - 1)) | w << RLO, lane (l' & 3) | r' << 2.
+//      Register rows are 68 floats apart (64 when RLO = 0) and the parts of the wavefronts 16 * 68 + 4 * 2^RLO,
+//      so that the 64 lanes of a store fall into 64 different banks; so do those of a load
+//   5. register stages RLO..3 (entry bits 10 and up)
+// Layout A in, layout B out -- or layout B in, layout A out: with 16 registers a lane the two exchanges are
+// the same map of (wavefront, register, lane); only the entry bits that the positions stand for differ, and
+// every index bit is transformed exactly once either way.
+// `ta` and `tb` are two buffers of tr_floats<K> floats; the caller swaps them from one call to the next, which
 // leaves one barrier per call: the transposition is written into the wavefront's own part of `ta` (last
 // read by this wavefront, in the exchange of the call before), the exchange into `tb` (last read as the
 // transposition buffer of the call before, by its owner, ahead of that call's barrier).
-constexpr int TR_ROW = 68;                                       // floats per register row of a transposition
-constexpr int TR_WAVE = 16 * TR_ROW + 4, TR_FLOATS = 16 * TR_WAVE;   // part of a wavefront: 1092 = 4 mod 64
+constexpr int TR_ROW = 68;   // floats per register row
+template <int K> constexpr int tr_wave = 16 * TR_ROW + (4 << Geo<K>::RLO);   // part of a wavefront
+template <int K> constexpr int tr_floats = Geo<K>::W * tr_wave<K>;
 __device__ __forceinline__ float tr_sigma(int lane) { return (__builtin_popcount(lane & 3) & 1) ? -1.0f : 1.0f; }
 
 template <int K>
 __device__ __forceinline__ void transform_transposed(float (&v)[16], float* ta, float* tb, int wave, int lane) {
-  static_assert(Geo<K>::R == 16 && Geo<K>::W == 16, "16 wavefronts of 16 registers");
+  // rows of the exchange: 68 floats apart where register bits come from the lane index (banks), else 64,
+  // which lets two rows share one LDS instruction (the st64 forms)
+  constexpr int RLO = Geo<K>::RLO, PART = tr_wave<K>, XROW = RLO ? TR_ROW : 64;
+  static_assert(Geo<K>::R == 16 && Geo<K>::Q >= 2 && Geo<K>::Q <= 4, "4, 8 or 16 wavefronts of 16 registers");
   reg_stages(v, 0, 4);
   lane_stage<0>(v, lane);
   lane_stage<1>(v, lane);
-  float* mine = ta + wave * TR_WAVE;
+  float* mine = ta + wave * PART;
 #pragma unroll
   for (int r = 0; r < 16; ++r) mine[r * TR_ROW + lane] = v[r];
   __builtin_amdgcn_wave_barrier();
@@ -331,46 +339,15 @@ __device__ __forceinline__ void transform_transposed(float (&v)[16], float* ta, 
 #pragma unroll
   for (int r = 0; r < 16; ++r) v[r] = back[r * 4];
   reg_stages(v, 0, 4);
-  float* to = tb + (lane >> 2) * TR_WAVE + wave * 64 + (lane & 3);
+  const int rho = lane >> 2;
+  float* to = tb + (rho >> RLO) * PART + ((rho & ((1 << RLO) - 1)) + (wave << RLO)) * XROW + (lane & 3);
 #pragma unroll
   for (int r = 0; r < 16; ++r) to[r * 4] = v[r];
   __syncthreads();
-  const float* from = tb + wave * TR_WAVE + lane;
+  const float* from = tb + wave * PART + lane;
 #pragma unroll
-  for (int r = 0; r < 16; ++r) v[r] = from[r * 64];
-  reg_stages(v, 0, 4);
-}
-
-// The same for tiles of 4 wavefronts x 16 registers (2^12 entries), two buffers of T4_FLOATS floats.  Layout A
-// in, layout B out -- or layout B in, layout A out: with this geometry both are the same map of (wavefront,
-// register, lane), only the entry bits that the positions stand for differ.
-//   after step 3 wavefront w, register r', lane l' holds entry (l' & 3) | r' << 2 | (l' >> 2) << 6 | w << 10;
-//   layout B wants wavefront (l' >> 4), register ((l' >> 2) & 3) | w << 2, lane (l' & 3) | r' << 2.
-// Rows of a register are 68 floats apart and the parts of the wavefronts 1104 (= 16 mod 64), so that the
-// 64 lanes of a store land in 64 different banks; so do those of a load (bank = lane + 4 register).
-constexpr int T4_WAVE = 16 * TR_ROW + 16, T4_FLOATS = 4 * T4_WAVE;
-template <int K>
-__device__ __forceinline__ void transform_transposed4(float (&v)[16], float* ta, float* tb, int wave, int lane) {
-  static_assert(Geo<K>::R == 16 && Geo<K>::W == 4, "4 wavefronts of 16 registers");
-  reg_stages(v, 0, 4);
-  lane_stage<0>(v, lane);
-  lane_stage<1>(v, lane);
-  float* mine = ta + wave * T4_WAVE;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) mine[r * TR_ROW + lane] = v[r];
-  __builtin_amdgcn_wave_barrier();
-  const float* back = mine + (lane >> 2) * TR_ROW + (lane & 3);
-#pragma unroll
-  for (int r = 0; r < 16; ++r) v[r] = back[r * 4];
-  reg_stages(v, 0, 4);
-  float* to = tb + (lane >> 4) * T4_WAVE + (((lane >> 2) & 3) + wave * 4) * TR_ROW + (lane & 3);
-#pragma unroll
-  for (int r = 0; r < 16; ++r) to[r * 4] = v[r];
-  __syncthreads();
-  const float* from = tb + wave * T4_WAVE + lane;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) v[r] = from[r * TR_ROW];
-  reg_stages(v, 2, 4);
+  for (int r = 0; r < 16; ++r) v[r] = from[r * XROW];
+  reg_stages(v, RLO, 4);
 }
 
 // ------------------------------------------------------------------ tile loads / stores
