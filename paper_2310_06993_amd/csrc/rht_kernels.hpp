@@ -336,7 +336,7 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_reduce_decode(PathArgs a) {
 // three separate calls give.  Blocks of up to 2^14 entries (one tile per block).
 //
 // Per worker: sign flip (layout A), transform to layout B, round, add under the received mask.  Tiles of
-// 4, 8 or 16 wavefronts x 16 registers use the transposed transform of rht_tile.hpp, in both directions.
+// 2, 4, 8 or 16 wavefronts x 16 registers use the transposed transform of rht_tile.hpp, in both directions.
 // PREFETCH: a second tile buffer, so that the next worker's tile is in flight during the transform (the
 // launcher decides from the size of the grid).  Inputs are read once: nontemporal loads.
 template <int K, class In, bool PREFETCH>
@@ -345,7 +345,7 @@ __device__ __forceinline__ void fused_tile(const PathArgs& a, u64 unit) {
   constexpr bool FULL = kShardTilesFull<K>;
   static_assert(!PREFETCH || R == 16, "a second tile buffer only with 16 entries per lane");
   static_assert(Geo<K>::PARTS == 1, "larger blocks use k_fused_pairs");
-  constexpr bool TRANSP = (R == 16 && Geo<K>::Q >= 2);    // transform_transposed, both ways
+  constexpr bool TRANSP = (R == 16 && Geo<K>::Q >= 1);    // transform_transposed, both ways
   constexpr int XF = TRANSP ? tr_floats<K> : T;
   constexpr int NBUF = TRANSP ? 2 : NB;
   __shared__ float xbuf[NBUF ? NBUF : 1][NBUF ? XF : 1];

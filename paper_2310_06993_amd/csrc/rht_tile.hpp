@@ -292,7 +292,7 @@ __device__ __forceinline__ void transform(float (&v)[Geo<K>::R], float* xbuf, in
 }
 
 // ------------------------------------------------------------------ transform with transposed lane bits
-// For tiles of W = 4, 8 or 16 wavefronts x 16 registers (2^12, 2^13, 2^14 entries).
+// For tiles of W = 2, 4, 8 or 16 wavefronts x 16 registers (2^11 ... 2^14 entries).
 // On MI355X a plain add/sub issues at twice the rate of anything with a DPP control, so the stages of lane
 // bits 2..5 cost three times a register stage (and those of bits 4, 5 an LDS-crossbar operation each on
 // top).  Here those four bits are made register bits by a transposition inside the wavefront (through a
@@ -327,7 +327,7 @@ __device__ __forceinline__ void transform_transposed(float (&v)[16], float* ta, 
   // rows of the exchange: 68 floats apart where register bits come from the lane index (banks), else 64,
   // which lets two rows share one LDS instruction (the st64 forms)
   constexpr int RLO = Geo<K>::RLO, PART = tr_wave<K>, XROW = RLO ? TR_ROW : 64;
-  static_assert(Geo<K>::R == 16 && Geo<K>::Q >= 2 && Geo<K>::Q <= 4, "4, 8 or 16 wavefronts of 16 registers");
+  static_assert(Geo<K>::R == 16 && Geo<K>::Q >= 1 && Geo<K>::Q <= 4, "2, 4, 8 or 16 wavefronts of 16 registers");
   reg_stages(v, 0, 4);
   lane_stage<0>(v, lane);
   lane_stage<1>(v, lane);
