@@ -398,6 +398,8 @@ or_status run_path(bool fused, const T* in, const uint32_t* masks, int N, u64 L,
                                              orhost::LAUNCH_FIRST, (uint4*)ws_cnt, seed, base >> 7, counters))
       return finish(e);
     a.sign_tab = (const u64*)ws_cnt;
+    if (k == 15)   // two tiles per block: the fused kernel decodes as well
+      return finish((bf16 ? t->fused_bf16 : t->fused_f32)(a, units, s, orhost::LAUNCH_LAST));
     a.mean_out = ws_f32;
     a.out = nullptr;
     if (hipError_t e = (bf16 ? t->fused_bf16 : t->fused_f32)(a, units, s, 0)) return finish(e);

@@ -452,8 +452,8 @@ void k_fused(PathArgs a) {
 // tiles: with u_q the signed input tiles and H_{2P} = [[H_P, H_P], [H_P, -H_P]],
 //     A = sum_{q <  P/2} H[h][q] u_q,   C = sum_{q >= P/2} H[h][q - P/2] u_q,   p_lo = A + C,  p_hi = A - C,
 // so the +-1 combination costs half the sign flips and adds per output of the one-tile-per-workgroup
-// form, and the inputs are read PARTS/2 times instead of PARTS times.  It stops at the fp32 mean
-// (layout B) in `mean_out`; k_decode finishes.
+// form, and the inputs are read PARTS/2 times instead of PARTS times.  With four tiles per block it stops at
+// the fp32 mean (layout B) in `mean_out` and k_decode_block finishes; with two it decodes its block itself.
 template <int K, class In>
 __global__ __launch_bounds__(Geo<K>::THREADS) void k_fused_pairs(PathArgs a) {
   constexpr int T = Geo<K>::T, R = Geo<K>::R, HB = Geo<K>::HB, PARTS = Geo<K>::PARTS, HP = PARTS / 2;
@@ -550,10 +550,36 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_fused_pairs(PathArgs a) {
   const float post = sigma * (scale_first ? 1.0f : a.scale);
   store_counts<K, true>(a.count_out, e_lo, L, wave, lane, cnt_lo, full_lo);
   finalize_mean(acc_lo, cnt_lo, full_lo, post);
-  store_tile<K, true, true>(a.mean_out, e_lo, L, wave, lane, acc_lo);
+  if constexpr (HP == 2) store_tile<K, true, true>(a.mean_out, e_lo, L, wave, lane, acc_lo);
   store_counts<K, true>(a.count_out, e_hi, L, wave, lane, cnt_hi, full_hi);
   finalize_mean(acc_hi, cnt_hi, full_hi, post);
-  store_tile<K, true, true>(a.mean_out, e_hi, L, wave, lane, acc_hi);
+  if constexpr (HP == 2) {
+    store_tile<K, true, true>(a.mean_out, e_hi, L, wave, lane, acc_hi);
+  } else {
+    // Two tiles per block: this workgroup holds the whole mean of its block and decodes it here (no trip of
+    // the mean through memory, no decode launch): the factor across the two tiles, the transform of each
+    // (layout B to layout A), scale, signs from the table (whose words are in layout-A order).
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const float s = acc_lo[r] + acc_hi[r];
+      acc_hi[r] = acc_lo[r] - acc_hi[r];
+      acc_lo[r] = s;
+    }
+    const float c = a.scale * sigma;
+    auto decode_tile = [&](float (&v)[R], int q) {
+      transform_transposed<K>(v, tbuf[flip], tbuf[flip ^ 1], wave, lane);
+      flip ^= 1;
+      table_ptr sg = (table_ptr)(a.sign_tab + ((((t0 + q) * T) + (u64)wave * Geo<K>::WAVE_ENTRIES) >> 6));
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const float x = v[r] * c;
+        v[r] = in_mask(sg[r]) ? -x : x;
+      }
+      store_tile<K, false, true, true>((In*)a.out, (t0 + q) * T, L, wave, lane, v);
+    };
+    decode_tile(acc_lo, 0);
+    decode_tile(acc_hi, 1);
+  }
 }
 
 // Several buckets of one launch shape class (same N, block size and type) in ONE launch: small buckets
