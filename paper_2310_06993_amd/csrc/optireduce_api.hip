@@ -189,8 +189,9 @@ __global__ __launch_bounds__(256) void k_masked_reduce_pairs(const float* __rest
   float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
   uint32_t cnt[4] = {0, 0, 0, 0};
   for (int g = 0; g < G; ++g) {
-    const f4 x = *(const f4*)(sums + (u64)g * L + e);
-    const uint32_t c4 = *(const uint32_t*)(counts + (u64)g * L + e);
+    // read once: nontemporal, as in k_masked_reduce
+    const f4 x = __builtin_nontemporal_load((const f4*)(sums + (u64)g * L + e));
+    const uint32_t c4 = __builtin_nontemporal_load((const uint32_t*)(counts + (u64)g * L + e));
     const uint32_t m = masks[(u64)g * words + (e >> 5)] >> sh;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
