@@ -388,11 +388,12 @@ def main():
                     for _ in range(2):
                         b.or_fused_path_batched(arr, nb, c.workers, c.block_log2, False)
                     torch.cuda.synchronize()
+                    reps = max(steps, 10)   # 1.5 ms a step: a few more for a steadier figure
                     t0 = time.perf_counter()
-                    for _ in range(steps):
+                    for _ in range(reps):
                         b.or_fused_path_batched(arr, nb, c.workers, c.block_log2, False)
                     torch.cuda.synchronize()
-                    ps = (time.perf_counter() - t0) / steps
+                    ps = (time.perf_counter() - t0) / reps
                     kn = ps / -(-nb // 64)
                     by = by_step / -(-nb // 64)
                     note = "all %d buckets per step through or_fused_path_batched (%d launches)" % (nb, -(-nb // 64))
