@@ -351,7 +351,8 @@ def test_errors_leave_outputs_untouched(b):
     assert bool((out == 7.0).all())
 
 
-@pytest.mark.parametrize("k,kind,long", [(12, "f32", 0), (10, "bf16", 0), (16, "f32", 0), (12, "f32", 20), (11, "bf16", 14)])
+@pytest.mark.parametrize("k,kind,long", [(12, "f32", 0), (10, "bf16", 0), (16, "f32", 0), (12, "f32", 20), (11, "bf16", 14),
+                                         (14, "f32", 0), (13, "bf16", 0), (15, "bf16", 0)])
 def test_batched_buckets_equal_single_calls(b, orc, k, kind, long):
     # buckets of different lengths in one call (more than 64 of them for k = 12: several launches)
     B = 1 << k
