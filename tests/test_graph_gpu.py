@@ -19,7 +19,7 @@ def _inputs(rng, N, L, bf16):
     return (t.bfloat16() if bf16 else t), pack_mask_np(recv)
 
 
-@pytest.mark.parametrize("k,bf16", [(12, False), (16, True)])
+@pytest.mark.parametrize("k,bf16", [(12, False), (16, True), (14, False), (15, True)])
 def test_fused_path_in_a_graph(k, bf16):
     import paper_2310_06993_amd.binding as b
     import oracle
