@@ -41,7 +41,8 @@
 // dense Hadamard products for every B <= 256 and against scipy's Sylvester
 // construction; H(Hx) = Bx bit-exactly on integer data; Parseval; exact
 // round trip with no drops; a hand-computed masked sum; the closed form for
-// one lost encoded entry; linearity and the slice property of the sign stream.
+// one lost encoded entry; linearity and the slice property of the sign stream;
+// both decodes with a bf16 result against the dense product rounded once.
 // Unpinned: the two MSE values the paper prints for its toy figure (the
 // figure's vectors are not in the text)  ->  "parity unpinned" for that figure.
 

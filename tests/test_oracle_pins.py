@@ -366,6 +366,66 @@ def test_decode_masked_is_decode_of_zero_filled(orc):
     assert not err[:B].any() and not err[2 * B:].any()
 
 
+def _bf16_bits_of(x64):
+    """fp64 -> fp32 -> bf16 bit patterns through torch's conversions (round to nearest even both times)."""
+    return torch.from_numpy(np.asarray(x64, np.float64).astype(np.float32)).to(torch.bfloat16).view(torch.int16) \
+        .numpy().view(np.uint16)
+
+
+def _equal_up_to_straddles(got, want):
+    """bf16 bit patterns equal, except where the fp64 value sits within rounding noise of a rounding
+    boundary (the butterfly and the dense product order their fp64 additions differently): at most one
+    entry in 10^4 may differ, and then by one unit in the last place."""
+    got, want = np.asarray(got, np.uint16), np.asarray(want, np.uint16)
+    bad = np.flatnonzero(got != want)
+    assert bad.size <= max(1, got.size // 10000), "%d of %d bf16 values differ" % (bad.size, got.size)
+    for j in bad:
+        assert abs(int(got[j]) - int(want[j])) == 1
+
+
+@pytest.mark.parametrize("k", [5, 8])
+def test_decode_to_bf16_is_the_dense_product_rounded_once(orc, k):
+    # Sec. 3.3 / Sec. 4 decode with a bf16 result: g = D B^(-1/2) H m written out with the dense matrix in
+    # fp64, then rounded to the output type (reading R7: bf16 only at the memory boundary)
+    seed, B = 21, 1 << k
+    base = 4 * max(B, 128)
+    n = 3 * B - 5
+    rng = np.random.default_rng(40 + k)
+    agg = (rng.standard_normal(orc.padded_len(n, k)) * 1e-3).astype(np.float32)
+    H = dense_hadamard(B) / np.sqrt(B)
+    s = signs_pm1(orc, seed, base, agg.size)
+    want = s * (H @ agg.astype(np.float64).reshape(-1, B).T).T.reshape(-1)
+    got = orc.rht_decode(agg, n, k, seed, base, out_dtype=np.uint16)
+    assert got.dtype == np.uint16 and got.shape == (n,)
+    _equal_up_to_straddles(got, _bf16_bits_of(want[:n]))
+    # a transposed operand, a dropped sign or a missing scale would be far outside one unit in the last place
+    wrong = s * (agg.astype(np.float64).reshape(-1, B) @ H.T).reshape(-1) * np.sqrt(B)
+    assert np.count_nonzero(got != _bf16_bits_of(wrong[:n])) > n // 2
+
+
+@pytest.mark.parametrize("k", [5, 8])
+def test_decode_masked_to_bf16_is_the_dense_product_of_the_zero_filled_mean(orc, k):
+    # second-stage loss (Sec. 3.1.1 broadcast stage; reading R15) with a bf16 result
+    seed, B = 22, 1 << k
+    base = 2 * max(B, 128)
+    n = 4 * B - 9
+    rng = np.random.default_rng(50 + k)
+    agg = (rng.standard_normal(orc.padded_len(n, k)) * 1e-3).astype(np.float32)
+    recv = rng.random(agg.size) > 0.07
+    poisoned = np.where(recv, agg, np.float32(np.nan))          # a lost slot is never read
+    H = dense_hadamard(B) / np.sqrt(B)
+    s = signs_pm1(orc, seed, base, agg.size)
+    want = s * (H @ np.where(recv, agg.astype(np.float64), 0.0).reshape(-1, B).T).T.reshape(-1)
+    got = orc.rht_decode_masked(poisoned, pack_mask(recv[None, :])[0], n, k, seed, base, out_dtype=np.uint16)
+    assert got.dtype == np.uint16 and got.shape == (n,)
+    _equal_up_to_straddles(got, _bf16_bits_of(want[:n]))
+    # all arrived: the plain bf16 decode, bit for bit; and it differs from the masked result where loss hit
+    full = np.full(agg.size // 32, 0xFFFFFFFF, np.uint32)
+    plain = orc.rht_decode(agg, n, k, seed, base, out_dtype=np.uint16)
+    assert np.array_equal(orc.rht_decode_masked(agg, full, n, k, seed, base, out_dtype=np.uint16), plain)
+    assert np.count_nonzero(plain != got) > n // 4
+
+
 def test_received_total_and_loss_fraction(orc):
     rng = np.random.default_rng(32)
     N, L = 6, 32 * 50
