@@ -5,9 +5,10 @@
 
 One step = one pass of the whole path (sign flip, blockwise Hadamard, masked sum and count, mean,
 inverse transform) over one synthetic batch: the N workers' raw slices of the shard this node owns,
-already resident in HBM.  The headline workload is the ResNet-50-sized configuration; input sets are
-rotated so that consecutive steps do not find their inputs in the 256 MB last-level cache.  Prints
-ONE JSON line.
+already resident in HBM.  The headline workload is the largest configuration, Llama-8B-sized (bf16, 8 workers,
+blocks of 2^16 entries, a 1.0e9-entry shard: 20 GB per step); the other four are reported beside it under
+`other_workloads`.  Input sets of the small workloads are rotated so that consecutive steps do not find their
+inputs in the 256 MB last-level cache.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -243,14 +244,34 @@ def profiled_traffic(workload):
         return None
 
 
+def roofline(cfg, L, nbytes, kern):
+    """Which roof: the path's minimum work per input entry is es + 1/8 + (es + 1)/N bytes and
+    k (N + 1)/N + 1 additions.  At the chip's peaks (8 TB/s; 256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz = 78.6e12
+    fp32 additions per second: an addition is half of the fused multiply-add that the published 157.3 TFLOP/s
+    counts) the bytes take longer than the additions for all five workloads, so HBM is the roof.  The second
+    figure is reported beside it because the kernels for 2^15 / 2^16 blocks spend more instructions than that
+    minimum (sign flips, conversions, rounding, count handling) and are limited by vector-ALU issue in practice."""
+    N, k = cfg.workers, cfg.block_log2
+    adds = (k * (N + 1) / N + 1.0) * N * L
+    peak_adds = 256 * 4 * 32 * 2.4e9
+    names = {True: "k_fused (one launch per step)",
+             False: "k_sign_table + k_fused_pairs + k_decode_block (one step; the fused kernel is >= 85 % of it)"}
+    return {"bound": "hbm", "achieved": nbytes / kern / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": nbytes / kern / 1e9 / HBM_PEAK_GBPS, "traffic": profiled_traffic(cfg.name),
+            "kernel": names[cfg.block_log2 <= 14], "avg_launch_us": kern * 1e6,
+            "ideal_ms_hbm": nbytes / (HBM_PEAK_GBPS * 1e9) * 1e3, "ideal_ms_alu": adds / peak_adds * 1e3,
+            "alu": {"algorithmic_fp32_additions": adds, "achieved_Tadd_per_s": adds / kern / 1e12,
+                    "peak_Tadd_per_s": peak_adds / 1e12, "frac": adds / kern / peak_adds}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=300)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=None, help="default: 20 for llama_8b, 300 for the small workloads")
+    ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--no-extra", action="store_true", help="skip the other model-sized workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
-    ap.add_argument("--workload", default="resnet50")
+    ap.add_argument("--workload", default="llama_8b")
     ap.add_argument("--timed-region-only", action="store_true",
                     help="only the warm-up and the timed region (for a profiler: every launch of the run is then "
                          "one of the serialized launches that `value` and `roofline` are about)")
@@ -273,6 +294,11 @@ def main():
     torch.cuda.set_device(device)
     cfg = wl.CONFIGS[args.workload]
     es = 4 if cfg.dtype == "f32" else 2
+    big = cfg.shard_len() * cfg.workers * es > (1 << 30)
+    if args.steps is None:
+        args.steps = 20 if big else 300
+    if args.warmup is None:
+        args.warmup = 3 if big else 20
 
     if args.calibrate_copy:
         src = torch.zeros(512 << 20, dtype=torch.uint8, device=device)
@@ -307,10 +333,7 @@ def main():
                                   cfg.loss * 100),
                    "entry_point": "or_fused_path" if cfg.dtype == "f32" else "or_fused_path_bf16",
                    "input_sets_rotated": nsets, "bytes_per_step": nbytes},
-        "roofline": {"bound": "hbm", "achieved": nbytes / kern / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": nbytes / kern / 1e9 / HBM_PEAK_GBPS, "traffic": profiled_traffic(cfg.name),
-                     "kernel": "k_fused" if cfg.block_log2 <= 14 else "k_sign_table + k_fused_pairs + k_decode_block",
-                     "avg_launch_us": kern * 1e6},
+        "roofline": roofline(cfg, L, nbytes, kern),
         "timed_region": "one replay of a HIP graph holding the %d launches, in order, on one stream" % args.steps,
         "plain_launches_ms_per_step": None if only else info["plain_launches_ms_per_step"],
     }
@@ -346,7 +369,7 @@ def main():
 
     if not args.no_extra:
         extra = []
-        for name, steps in (("bert_large", 20), ("gpt2_xl", 3), ("llama_8b", 5)):
+        for name, steps in (("tiny", 300), ("resnet50", 300), ("bert_large", 20), ("gpt2_xl", 3), ("llama_8b", 5)):
             if name == args.workload:
                 continue
             c = wl.CONFIGS[name]
@@ -382,22 +405,43 @@ def main():
                                   "GB_per_s": by_step / ps4 / 1e9, "entries_per_s": ent / ps4, "ms_per_step": ps4 * 1e3,
                                   "frac_hbm_peak": by_step / ps4 / 1e9 / HBM_PEAK_GBPS, "input_sets_rotated": ns,
                                   "note": "%d launches per step, round-robin over 4 streams" % nb})
-                    # the same buckets through the batched entry point: 64 buckets per launch
-                    arr = b.make_buckets([(st[j % ns][0], st[j % ns][1], st[j % ns][2], st[j % ns][3], Lb, c.seed,
+                    # the same buckets through the batched entry points: up to 64 buckets per launch.  Inputs are
+                    # the rotated sets; every bucket has outputs of its own (buckets of a call must not share any)
+                    outs = torch.empty((nb, Lb), dtype=torch.float32, device=device)
+                    cnts = torch.empty((nb, Lb), dtype=torch.uint8, device=device)
+                    sums = torch.empty((nb, Lb), dtype=torch.float32, device=device)
+                    arr = b.make_buckets([(st[j % ns][0], st[j % ns][1], outs[j], cnts[j], Lb, c.seed,
                                            (j % ns % c.workers) * Lb) for j in range(nb)])
-                    for _ in range(2):
-                        b.or_fused_path_batched(arr, nb, c.workers, c.block_log2, False)
-                    torch.cuda.synchronize()
+                    sarr = b.make_stage_buckets([(st[j % ns][0], st[j % ns][1], sums[j], cnts[j], outs[j], Lb, c.seed,
+                                                  (j % ns % c.workers) * Lb) for j in range(nb)])
                     reps = max(steps, 10)   # 1.5 ms a step: a few more for a steadier figure
-                    t0 = time.perf_counter()
-                    for _ in range(reps):
-                        b.or_fused_path_batched(arr, nb, c.workers, c.block_log2, False)
-                    torch.cuda.synchronize()
-                    ps = (time.perf_counter() - t0) / reps
+
+                    def timed(fn):
+                        for _ in range(2):
+                            fn()
+                        torch.cuda.synchronize()
+                        t0 = time.perf_counter()
+                        for _ in range(reps):
+                            fn()
+                        torch.cuda.synchronize()
+                        return (time.perf_counter() - t0) / reps
+
+                    N_, k_, Lall = c.workers, c.block_log2, Lb * nb
+                    t_red = timed(lambda: b.or_masked_reduce_batched(sarr, nb, N_, False))
+                    t_fdec = timed(lambda: b.or_finalize_decode_batched(sarr, nb, k_, False))
+                    t_rdec = timed(lambda: b.or_reduce_decode_batched(arr, nb, N_, k_, False))
+                    extra.append({"workload": name + " (separate calls, batched)",
+                                  "masked_reduce_GB_per_s": (N_ * Lall * 4 + N_ * Lall // 8 + 5 * Lall) / t_red / 1e9,
+                                  "finalize_decode_GB_per_s": Lall * 9 / t_fdec / 1e9,
+                                  "reduce_decode_GB_per_s": by_step / t_rdec / 1e9,
+                                  "note": "all %d buckets per call: or_masked_reduce_batched, or_finalize_decode_batched, "
+                                          "or_reduce_decode_batched (%d launches each)" % (nb, -(-nb // 64))})
+                    ps = timed(lambda: b.or_fused_path_batched(arr, nb, c.workers, c.block_log2, False))
                     kn = ps / -(-nb // 64)
                     by = by_step / -(-nb // 64)
                     note = "all %d buckets per step through or_fused_path_batched (%d launches)" % (nb, -(-nb // 64))
                     name = name + " (batched)"
+                    del outs, cnts, sums
                 else:
                     ps, kn, by, ns, st = time_fused(wl, b, c, device, steps, 2)
                     by_step, ent, note = by, c.workers * c.shard_len(), "one launch per step"
@@ -405,8 +449,12 @@ def main():
                        "ms_per_step": ps * 1e3, "avg_launch_us": kn * 1e6,
                        "launch_GB_per_s": by / kn / 1e9, "frac_hbm_peak": by / kn / 1e9 / HBM_PEAK_GBPS,
                        "input_sets_rotated": ns, "note": note}
+                if name == "tiny":
+                    row["note"] = ("correctness configuration: %d input sets of %.1f MB stay in the 256 MB last-level "
+                                   "cache, so this is not an HBM figure" % (ns, by / 1e6))
+                    row["cache_resident"] = True
                 if not c.bucket_entries:
-                    row["three_call_path"] = time_three_calls(wl, b, c, st, iters=5)
+                    row["three_call_path"] = time_three_calls(wl, b, c, st, iters=5 if by > (1 << 28) else 50)
                 extra.append(row)
                 del st
                 torch.cuda.empty_cache()

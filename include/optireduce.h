@@ -10,7 +10,9 @@
  *     state between calls and may be called from several host threads.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call validates its
  *     arguments on the host, enqueues its kernels on that stream and returns; it never synchronises.
- *     On any error nothing is enqueued and no output is touched.
+ *     Every argument error (status below OR_ERR_HIP) is found before anything is enqueued: no output
+ *     is touched.  OR_ERR_HIP reports a launch that the runtime refused; an entry point that enqueues
+ *     several kernels may by then have enqueued the earlier ones, so treat its outputs as undefined.
  *   - Vectors are contiguous.  fp32 data is `float`; bf16 data is passed as uint16_t bit patterns.
  *     Data pointers must be 16-byte aligned, mask pointers 4-byte aligned.
  *   - block_log2 = k selects the transform block B = 2^k, OR_MIN_LOG2 <= k <= OR_MAX_LOG2.
@@ -68,8 +70,9 @@ int or_last_hip_error(void);
 /* Measurement hook (not part of the method).  Arms two caller-created hipEvent_t (either may be NULL)
  * for the NEXT entry-point call made by this thread: `start_event` is attached to the first kernel
  * that call enqueues and receives that kernel's begin timestamp, `stop_event` to the last one and
- * receives its end timestamp, so hipEventElapsedTime(start, stop) after a synchronise is the device
- * time of the call without launch gaps.  The arming is consumed by that call whether it succeeds or
+ * receives its end timestamp (for a call that enqueues several kernels: the first kernel of all and the
+ * last of all), so hipEventElapsedTime(start, stop) after a synchronise is the device time of the call
+ * without launch gaps.  The arming is consumed by that call whether it succeeds or
  * not; a call that enqueues nothing leaves the events unrecorded. */
 or_status or_time_next_call(void* start_event, void* stop_event);
 
@@ -103,7 +106,10 @@ or_status or_rht_decode_at(const float* agg, uint64_t n, int block_log2, uint64_
 or_status or_rht_decode_bf16(const float* agg, uint64_t n, int block_log2, uint64_t seed, uint64_t base_index,
                              uint16_t* out, void* stream);
 
-/* ---- fused forms (same results as the calls above chained, fewer trips through memory) --------
+/* ---- fused forms (the calls above chained, with fewer trips through memory) -------------------
+ * Counts are identical to those of the chained calls; values agree with them within the tolerance
+ * of the path (relative L2 1e-6 for fp32, 1e-2 for bf16): the fused kernels take the mean with a
+ * reciprocal and a multiply where or_finalize divides, and sum in their own order.
  * "Averages" (Sec. 3.1.1) is read as sum / number received, 0 where nothing was received.
  *
  * or_finalize_decode: mean = sum / count, then decode.  sum, count: or_padded_len(n) entries. */
@@ -192,8 +198,9 @@ or_status or_masked_reduce_pairs(const float* sums, const uint8_t* counts, const
  * bucket (Sec. 3.1.1 footnote: 25 MB by default) is only about a hundred tiles per shard, far too few
  * to fill the GPU alone.  `buckets` is a HOST array, read before the call returns; the device
  * pointers in it follow the rules of or_fused_path (grads/out are float or bf16 bits per `bf16`).
- * Every bucket is validated before anything is enqueued.  For block_log2 > 14 the buckets are run one
- * after the other and `workspace` must cover the largest or_workspace_bytes() among them. */
+ * Every bucket is validated before anything is enqueued; no output of one bucket may overlap anything
+ * of another bucket (OR_ERR_SHAPE).  Buckets of length 0 are skipped.  For block_log2 > 14 the buckets
+ * are run one after the other and `workspace` must cover the largest or_workspace_bytes() among them. */
 typedef struct or_bucket {
   const void* grads;      /* [N][shard_len] raw slices                  */
   const uint32_t* masks;  /* [N][shard_len/32]                          */
@@ -205,6 +212,40 @@ typedef struct or_bucket {
 } or_bucket;
 or_status or_fused_path_batched(const or_bucket* buckets, int n_buckets, int N, int block_log2, int bf16,
                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* The same with the loss statistic of Sec. 3.4 taken inside the same kernels: totals (device, 8-byte
+ * aligned, n_buckets entries, or NULL) receives per bucket the number of (worker, entry) arrivals, the
+ * value or_received_total gives for that bucket's counts; totals[j] of an empty bucket is 0.  One
+ * bucket is the case n_buckets = 1. */
+or_status or_fused_path_batched_monitored(const or_bucket* buckets, int n_buckets, int N, int block_log2, int bf16,
+                                          uint64_t* totals, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- the separate calls on several buckets (Sec. 3.1.1 footnote: DDP hands over 25 MB buckets; one
+ * bucket per launch leaves most of the GPU idle).  Same descriptor scheme, same validation rules.
+ *
+ * or_reduce_decode_batched: or_reduce_decode / _bf16 per bucket; or_bucket.grads holds the ENCODED
+ * shards.  totals as in or_fused_path_batched_monitored (may be NULL). */
+or_status or_reduce_decode_batched(const or_bucket* buckets, int n_buckets, int N, int block_log2, int bf16,
+                                   uint64_t* totals, void* workspace, size_t workspace_bytes, void* stream);
+
+/* or_masked_reduce_batched: or_masked_reduce / _bf16 per bucket (reads shards, masks; writes sum, count;
+ * out, seed and base_index are ignored).
+ * or_finalize_decode_batched: or_finalize_decode / _bf16 per bucket (reads sum, count; writes out;
+ * shards and masks are ignored); every shard_len must be a whole number of blocks; out == sum is
+ * allowed for fp32. */
+typedef struct or_stage_bucket {
+  const void* shards;     /* [N][shard_len] encoded shards (float or bf16 bits per `bf16`) */
+  const uint32_t* masks;  /* [N][shard_len/32]                                            */
+  float* sum;             /* shard_len fp32 sums                                          */
+  uint8_t* count;         /* shard_len counts                                             */
+  void* out;              /* shard_len decoded entries (float or bf16 bits per `bf16`)    */
+  uint64_t shard_len;
+  uint64_t seed;
+  uint64_t base_index;
+} or_stage_bucket;
+or_status or_masked_reduce_batched(const or_stage_bucket* buckets, int n_buckets, int N, int bf16, void* stream);
+or_status or_finalize_decode_batched(const or_stage_bucket* buckets, int n_buckets, int block_log2, int bf16,
+                                     void* stream);
 
 #ifdef __cplusplus
 }

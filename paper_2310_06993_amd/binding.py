@@ -45,6 +45,10 @@ _SIGS = {
     "or_fused_path": (_int, [_p, _p, _int, _u64, _int, _u64, _u64, _p, _p, _p, _sz, _p]),
     "or_fused_path_bf16": (_int, [_p, _p, _int, _u64, _int, _u64, _u64, _p, _p, _p, _sz, _p]),
     "or_fused_path_batched": (_int, [_p, _int, _int, _int, _int, _p, _sz, _p]),
+    "or_fused_path_batched_monitored": (_int, [_p, _int, _int, _int, _int, _p, _p, _sz, _p]),
+    "or_reduce_decode_batched": (_int, [_p, _int, _int, _int, _int, _p, _p, _sz, _p]),
+    "or_masked_reduce_batched": (_int, [_p, _int, _int, _int, _p]),
+    "or_finalize_decode_batched": (_int, [_p, _int, _int, _int, _p]),
     "or_finalize": (_int, [_p, _p, _u64, _p, _p]),
     "or_finalize_bf16": (_int, [_p, _p, _u64, _p, _p]),
     "or_received_total": (_int, [_p, _u64, _p, _p]),
@@ -66,6 +70,13 @@ class or_loss_policy(C.Structure):
 class or_bucket(C.Structure):
     _fields_ = [("grads", _p), ("masks", _p), ("out", _p), ("count_out", _p),
                 ("shard_len", _u64), ("seed", _u64), ("base_index", _u64)]
+
+
+class or_stage_bucket(C.Structure):
+    _fields_ = [("shards", _p), ("masks", _p), ("sum", _p), ("count", _p), ("out", _p),
+                ("shard_len", _u64), ("seed", _u64), ("base_index", _u64)]
+
+
 for _name, (_res, _args) in _SIGS.items():
     _f = getattr(lib, _name)
     _f.restype, _f.argtypes = _res, _args
@@ -211,6 +222,40 @@ def or_fused_path_batched(buckets, n_buckets, N, block_log2, bf16, workspace=Non
     w, wb = _ws(workspace)
     _check(lib.or_fused_path_batched(C.cast(buckets, _p), n_buckets, N, block_log2, int(bool(bf16)), w, wb,
                                      _stream(stream)), "or_fused_path_batched")
+
+
+def or_fused_path_batched_monitored(buckets, n_buckets, N, block_log2, bf16, totals, workspace=None, stream=None):
+    """totals: an int64 device tensor of n_buckets entries, or None."""
+    w, wb = _ws(workspace)
+    _check(lib.or_fused_path_batched_monitored(C.cast(buckets, _p), n_buckets, N, block_log2, int(bool(bf16)),
+                                               _ptr(totals), w, wb, _stream(stream)),
+           "or_fused_path_batched_monitored")
+
+
+def or_reduce_decode_batched(buckets, n_buckets, N, block_log2, bf16, totals=None, workspace=None, stream=None):
+    w, wb = _ws(workspace)
+    _check(lib.or_reduce_decode_batched(C.cast(buckets, _p), n_buckets, N, block_log2, int(bool(bf16)),
+                                        _ptr(totals), w, wb, _stream(stream)), "or_reduce_decode_batched")
+
+
+def make_stage_buckets(items):
+    """items: iterable of (shards, masks, sum, count, out, shard_len, seed, base_index) with device tensors
+    (or None where the call ignores the field) -> a host array of or_stage_bucket."""
+    items = list(items)
+    arr = (or_stage_bucket * len(items))()
+    for j, (sh, m, t, c, o, L, seed, base) in enumerate(items):
+        arr[j] = or_stage_bucket(_ptr(sh), _ptr(m), _ptr(t), _ptr(c), _ptr(o), L, seed, base)
+    return arr
+
+
+def or_masked_reduce_batched(buckets, n_buckets, N, bf16, stream=None):
+    _check(lib.or_masked_reduce_batched(C.cast(buckets, _p), n_buckets, N, int(bool(bf16)), _stream(stream)),
+           "or_masked_reduce_batched")
+
+
+def or_finalize_decode_batched(buckets, n_buckets, block_log2, bf16, stream=None):
+    _check(lib.or_finalize_decode_batched(C.cast(buckets, _p), n_buckets, block_log2, int(bool(bf16)),
+                                          _stream(stream)), "or_finalize_decode_batched")
 
 
 def or_finalize(total, count, shard_len, mean_out, stream=None):

@@ -70,6 +70,17 @@ OR_SPLIT_LAUNCHER(mdec_bf16, OR_XFORM_LAUNCHER, OR_DEC(bf16_t, false, true, true
 constexpr int KR = (K == 13 || K == 14) ? K + kWide : K;
 OR_LAUNCHER_T(rdec_f32, (k_reduce_decode<KR, float, float>), Geo<KR>::THREADS)
 OR_LAUNCHER_T(rdec_bf16, (k_reduce_decode<KR, bf16_t, bf16_t>), Geo<KR>::THREADS)
+// several buckets per launch: `units` = tiles of all the buckets together
+#define OR_BATCH_LAUNCHER(name, kernel, threads)                                             \
+  hipError_t name(const BatchArgs& a, unsigned long long units, hipStream_t s, int pos) {   \
+    if (units == 0) return hipSuccess;                                                       \
+    if (units > 0x7FFFFFFFull) return hipErrorInvalidValue;                                  \
+    return launch_kernel(kernel, dim3((unsigned)units), dim3(threads), s, pos, a);           \
+  }
+OR_BATCH_LAUNCHER(rdecb_f32, (k_reduce_decode_batched<KR, float>), Geo<KR>::THREADS)
+OR_BATCH_LAUNCHER(rdecb_bf16, (k_reduce_decode_batched<KR, bf16_t>), Geo<KR>::THREADS)
+OR_BATCH_LAUNCHER(fdecb_f32, (k_finalize_decode_batched<K, float>), G::THREADS)
+OR_BATCH_LAUNCHER(fdecb_bf16, (k_finalize_decode_batched<K, bf16_t>), G::THREADS)
 // The fused kernels come in two forms where a lane holds 16 entries: with a second tile buffer (the next
 // worker's tile travels while this one is transformed), which shortens the chain of dependent steps of a
 // workgroup and wins while a launch puts at most three workgroups on each of the 256 CUs, and without,
@@ -120,9 +131,9 @@ extern const KernelTable OR_CAT(or_kernel_table_, OR_K) = {
 #endif
     fus_f32, fus_bf16,
 #if OR_K <= 14
-    fusb_f32, fusb_bf16
+    fusb_f32, fusb_bf16, rdecb_f32, rdecb_bf16, fdecb_f32, fdecb_bf16
 #else
-    nullptr, nullptr
+    nullptr, nullptr, nullptr, nullptr, nullptr, nullptr
 #endif
 };
 #endif

@@ -43,10 +43,9 @@ thread_local int g_last_hip_error = 0;
 #define OR_NT_REDUCE true
 #endif
 template <class Wire, int VEC>
-__global__ __launch_bounds__(256) void k_masked_reduce(const Wire* __restrict__ shards,
-                                                       const uint32_t* __restrict__ masks, int N, u64 L,
-                                                       float* __restrict__ sum_out, uint8_t* __restrict__ count_out) {
-  const u64 e = ((u64)blockIdx.x * 256 + threadIdx.x) * VEC;
+__device__ __forceinline__ void masked_reduce_at(const Wire* __restrict__ shards, const uint32_t* __restrict__ masks,
+                                                 int N, u64 L, float* __restrict__ sum_out,
+                                                 uint8_t* __restrict__ count_out, u64 e) {
   if (e >= L) return;
   typedef Wire vec_t __attribute__((ext_vector_type(VEC)));
   const u64 words = L >> 5;
@@ -101,6 +100,37 @@ __global__ __launch_bounds__(256) void k_masked_reduce(const Wire* __restrict__ 
 }
 
 template <class Wire, int VEC>
+__global__ __launch_bounds__(256) void k_masked_reduce(const Wire* __restrict__ shards,
+                                                       const uint32_t* __restrict__ masks, int N, u64 L,
+                                                       float* __restrict__ sum_out, uint8_t* __restrict__ count_out) {
+  masked_reduce_at<Wire, VEC>(shards, masks, N, L, sum_out, count_out, ((u64)blockIdx.x * 256 + threadIdx.x) * VEC);
+}
+
+// several buckets in one launch (a 25 MiB bucket is a few hundred workgroups here): descriptors in the kernel
+// arguments; workgroup x serves entries of bucket j from (x - start[j]) * 256 * VEC on
+struct ReduceBucket {
+  const void* shards;
+  const uint32_t* masks;
+  float* sum;
+  uint8_t* count;
+  u64 L;
+};
+struct ReduceBatch {
+  int n, N;
+  uint32_t start[ordev::kMaxBatch + 1];
+  ReduceBucket b[ordev::kMaxBatch];
+};
+static_assert(sizeof(ReduceBatch) <= 4096, "kernel arguments are limited to 4 KB");
+template <class Wire, int VEC>
+__global__ __launch_bounds__(256) void k_masked_reduce_batched(ReduceBatch rb) {
+  const uint32_t x = blockIdx.x;
+  int j = 0;
+  while (j + 1 < rb.n && rb.start[j + 1] <= x) ++j;
+  masked_reduce_at<Wire, VEC>((const Wire*)rb.b[j].shards, rb.b[j].masks, rb.N, rb.b[j].L, rb.b[j].sum, rb.b[j].count,
+                              ((u64)(x - rb.start[j]) * 256 + threadIdx.x) * VEC);
+}
+
+template <class Wire, int VEC>
 hipError_t launch_masked_reduce(const void* shards, const uint32_t* masks, int N, u64 L, float* sum_out,
                                 uint8_t* count_out, hipStream_t s, int pos) {
   if (L == 0) return hipSuccess;
@@ -139,6 +169,10 @@ __global__ __launch_bounds__(256) void k_finalize(const float* __restrict__ sum,
 }
 
 __global__ void k_zero_u64(unsigned long long* p) { *p = 0; }
+__global__ __launch_bounds__(256) void k_zero_u64n(unsigned long long* p, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
 
 // Sign bits of n_counters * 128 consecutive entries as a table: the Philox output for counter
 // first_counter + c, 16 bytes, at tab + 16 c -- so bit j of 64-bit word w is the sign of entry 64 w + j
@@ -368,21 +402,25 @@ or_status check_path(const void* in, const uint32_t* masks, int N, u64 L, int k,
   return OR_OK;
 }
 
-// enqueue one checked shard: T = float or uint16_t (bf16 bits)
+// enqueue one checked shard: T = float or uint16_t (bf16 bits).  `allow` = which of this entry point's first /
+// last launches this shard may be (timing events ride on those only); `total`, if not null, is expected to be
+// zero already and receives the number of arrivals.
 template <class T>
 or_status run_path(bool fused, const T* in, const uint32_t* masks, int N, u64 L, int k, u64 seed, u64 base, T* out,
-                   uint8_t* count_out, void* ws, void* stream, bool bf16) {
+                   uint8_t* count_out, void* ws, void* stream, bool bf16, int allow = orhost::LAUNCH_ONLY,
+                   unsigned long long* total = nullptr) {
   if (L == 0) return OR_OK;
   const size_t need = workspace_bytes(L, k);
   const orhost::KernelTable* t = orhost::table_for_class(class_of(k));
   hipStream_t s = (hipStream_t)stream;
   const u64 units = (L + ((u64)1 << t->tile_log2) - 1) >> t->tile_log2;
+  const int first = orhost::LAUNCH_FIRST & allow, last = orhost::LAUNCH_LAST & allow;
   PathArgs a = {};
   a.in = in; a.masks = masks; a.out = out; a.count_out = count_out; a.n = L; a.n_pad = L; a.seed = seed; a.base = base;
-  a.N = N; a.k = k; a.scale = scale_of(k);
+  a.N = N; a.k = k; a.scale = scale_of(k); a.total_out = total;
   if (!need) {
     orhost::launch_fn f = fused ? (bf16 ? t->fused_bf16 : t->fused_f32) : (bf16 ? t->reduce_decode_bf16 : t->reduce_decode_f32);
-    return finish(f(a, units, s, orhost::LAUNCH_ONLY));
+    return finish(f(a, units, s, first | last));
   }
   // a block spans several tiles: stop at the mean (or sum and count) in the workspace, then decode it
   float* ws_f32 = (float*)ws;
@@ -396,22 +434,28 @@ or_status run_path(bool fused, const T* in, const uint32_t* masks, int N, u64 L,
     const u64 counters = L >> 7;
     if ((counters + 255) / 256 > 0x7FFFFFFFull) return OR_ERR_SHAPE;
     if (hipError_t e = orhost::launch_kernel(k_sign_table, dim3((unsigned)((counters + 255) / 256)), dim3(256), s,
-                                             orhost::LAUNCH_FIRST, (uint4*)ws_cnt, seed, base >> 7, counters))
+                                             first, (uint4*)ws_cnt, seed, base >> 7, counters))
       return finish(e);
     a.sign_tab = (const u64*)ws_cnt;
     if (k == 15)   // two tiles per block: the fused kernel decodes as well
-      return finish((bf16 ? t->fused_bf16 : t->fused_f32)(a, units, s, orhost::LAUNCH_LAST));
+      return finish((bf16 ? t->fused_bf16 : t->fused_f32)(a, units, s, last));
     a.mean_out = ws_f32;
     a.out = nullptr;
     if (hipError_t e = (bf16 ? t->fused_bf16 : t->fused_f32)(a, units, s, 0)) return finish(e);
-    return finish((bf16 ? t->decode_bf16 : t->decode_f32)(d, units, s, orhost::LAUNCH_LAST));
+    return finish((bf16 ? t->decode_bf16 : t->decode_f32)(d, units, s, last));
   }
   uint8_t* cnt = count_out ? count_out : ws_cnt;
   constexpr int VEC = 16 / sizeof(T);
-  if (hipError_t e = launch_masked_reduce<T, VEC>(in, masks, N, L, ws_f32, cnt, s, orhost::LAUNCH_FIRST))
-    return finish(e);
+  if (hipError_t e = launch_masked_reduce<T, VEC>(in, masks, N, L, ws_f32, cnt, s, first)) return finish(e);
   d.count_in = cnt;
-  return finish((bf16 ? t->finalize_decode_bf16 : t->finalize_decode_f32)(d, units, s, orhost::LAUNCH_LAST));
+  if (total) {
+    u64 blocks = (L / 16 + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    if (hipError_t e = orhost::launch_kernel(k_received_total, dim3((unsigned)(blocks ? blocks : 1)), dim3(256), s, 0,
+                                             (const uint8_t*)cnt, L, total))
+      return finish(e);
+  }
+  return finish((bf16 ? t->finalize_decode_bf16 : t->finalize_decode_f32)(d, units, s, last));
 }
 
 template <class T>
@@ -477,40 +521,113 @@ or_status pairs_impl(const float* sums, const uint8_t* counts, const uint32_t* m
                                       orhost::LAUNCH_ONLY, sums, counts, masks, G, L, sum_out, count_out));
 }
 
-or_status batched_impl(const or_bucket* buckets, int n, int N, int k, bool bf16, void* ws, size_t ws_bytes, void* stream) {
+// How the non-empty buckets of a batched call are spread over launches: as few launches as the descriptor
+// limit allows, the buckets divided evenly among them.
+struct BatchPlan {
+  int nonempty, launches, per_launch;
+};
+BatchPlan plan_batches(int nonempty) {
+  BatchPlan p = {nonempty, 0, 0};
+  if (nonempty > 0) {
+    p.launches = (nonempty + ordev::kMaxBatch - 1) / ordev::kMaxBatch;
+    p.per_launch = (nonempty + p.launches - 1) / p.launches;
+  }
+  return p;
+}
+
+// no output of one bucket may touch anything of another bucket (the buckets of a launch run concurrently)
+struct Span { const void* p; u64 bytes; bool written; };
+template <int NS>
+or_status check_disjoint(const Span (&a)[NS], const Span (&b)[NS]) {
+  for (int i = 0; i < NS; ++i)
+    for (int j = 0; j < NS; ++j)
+      if ((a[i].written || b[j].written) && a[i].p && b[j].p && a[i].bytes && b[j].bytes &&
+          ranges_overlap(a[i].p, a[i].bytes, b[j].p, b[j].bytes))
+        return OR_ERR_SHAPE;
+  return OR_OK;
+}
+
+hipError_t zero_totals(unsigned long long* totals, int n, hipStream_t s, int pos) {
+  return orhost::launch_kernel(k_zero_u64n, dim3((unsigned)((n + 255) / 256)), dim3(256), s, pos, totals, n);
+}
+
+// or_fused_path_batched* (fused = true) and or_reduce_decode_batched (fused = false)
+or_status path_batched_impl(bool fused, const or_bucket* buckets, int n, int N, int k, bool bf16,
+                            unsigned long long* totals, void* ws, size_t ws_bytes, void* stream) {
   DisarmOnExit disarm;
   if (n < 0) return OR_ERR_SHAPE;
   if (n == 0) return OR_OK;
   if (!buckets) return OR_ERR_NULL;
-  const int es = bf16 ? 2 : 4;
-  for (int j = 0; j < n; ++j) {   // every bucket is checked before anything is enqueued
+  if (totals && !aligned(totals, 8)) return OR_ERR_ALIGN;
+  const u64 es = bf16 ? 2 : 4;
+  const Span tot = {totals, totals ? (u64)n * 8 : 0, true};
+  // ---- every bucket is checked before anything is enqueued
+  int nonempty = 0;
+  for (int j = 0; j < n; ++j) {
     const or_bucket& q = buckets[j];
-    if (or_status s = check_path(q.grads, q.masks, N, q.shard_len, k, q.base_index, q.out, q.count_out, ws, ws_bytes, es))
+    if (or_status s = check_path(q.grads, q.masks, N, q.shard_len, k, q.base_index, q.out, q.count_out, ws, ws_bytes, (int)es))
       return s;
+    if (q.shard_len == 0) continue;
+    ++nonempty;
+    const u64 L = q.shard_len;
+    const Span a[5] = {{q.grads, (u64)N * L * es, false}, {q.masks, (u64)N * (L / 8), false}, {q.out, L * es, true},
+                       {q.count_out, L, true}, {ws, workspace_bytes(L, k), true}};
+    const Span t5[5] = {tot, {}, {}, {}, {}};
+    if (check_disjoint(a, t5)) return OR_ERR_SHAPE;
+    for (int i = 0; i < j; ++i) {
+      const or_bucket& r = buckets[i];
+      const u64 M = r.shard_len;
+      const Span b[5] = {{r.grads, (u64)N * M * es, false}, {r.masks, (u64)N * (M / 8), false}, {r.out, M * es, true},
+                         {r.count_out, M, true}, {}};
+      if (check_disjoint(a, b)) return OR_ERR_SHAPE;
+    }
   }
   const orhost::KernelTable* t = orhost::table_for_class(class_of(k));
-  orhost::batch_fn f = bf16 ? t->fused_batched_bf16 : t->fused_batched_f32;
+  orhost::batch_fn f = fused ? (bf16 ? t->fused_batched_bf16 : t->fused_batched_f32)
+                             : (bf16 ? t->reduce_decode_batched_bf16 : t->reduce_decode_batched_f32);
+  const BatchPlan plan = plan_batches(nonempty);
+  hipStream_t s = (hipStream_t)stream;
+  // ---- enqueue: the entry point's very first launch carries the start event, its last one the stop event
+  bool first_pending = true;
+  if (totals) {
+    if (hipError_t e = zero_totals(totals, n, s, nonempty ? orhost::LAUNCH_FIRST : orhost::LAUNCH_ONLY)) return finish(e);
+    first_pending = false;
+  }
+  if (!nonempty) return OR_OK;
+  int seen = 0;
   if (!f) {   // blocks above 2^14: one bucket after the other, sharing the workspace in stream order
     for (int j = 0; j < n; ++j) {
       const or_bucket& q = buckets[j];
-      or_status s = bf16 ? run_path<uint16_t>(true, (const uint16_t*)q.grads, q.masks, N, q.shard_len, k, q.seed,
-                                              q.base_index, (uint16_t*)q.out, q.count_out, ws, stream, true)
-                         : run_path<float>(true, (const float*)q.grads, q.masks, N, q.shard_len, k, q.seed, q.base_index,
-                                           (float*)q.out, q.count_out, ws, stream, false);
-      if (s) return s;
+      if (q.shard_len == 0) continue;
+      ++seen;
+      const int allow = (first_pending ? orhost::LAUNCH_FIRST : 0) | (seen == nonempty ? orhost::LAUNCH_LAST : 0);
+      first_pending = false;
+      unsigned long long* one = totals ? totals + j : nullptr;
+      or_status st = bf16 ? run_path<uint16_t>(fused, (const uint16_t*)q.grads, q.masks, N, q.shard_len, k, q.seed,
+                                               q.base_index, (uint16_t*)q.out, q.count_out, ws, stream, true, allow, one)
+                          : run_path<float>(fused, (const float*)q.grads, q.masks, N, q.shard_len, k, q.seed, q.base_index,
+                                            (float*)q.out, q.count_out, ws, stream, false, allow, one);
+      if (st) return st;
     }
     return OR_OK;
   }
-  for (int j0 = 0; j0 < n; j0 += ordev::kMaxBatch) {
+  for (int j = 0; seen < nonempty;) {
     ordev::BatchArgs ba = {};
-    ba.N = N; ba.k = k; ba.scale = scale_of(k);
+    ba.N = N; ba.k = k; ba.scale = scale_of(k); ba.totals = totals;
     u64 tiles = 0;
     int m = 0;
-    for (int j = j0; j < n && m < ordev::kMaxBatch; ++j) {
+    for (; j < n && m < plan.per_launch; ++j) {
       const or_bucket& q = buckets[j];
-      if (q.shard_len == 0) continue;
+      if (q.shard_len == 0) {
+        if (totals && m) { ++j; break; }   // totals[first + m] is bucket first + m: a run of buckets without a gap
+        continue;
+      }
       const u64 units = (q.shard_len + ((u64)1 << t->tile_log2) - 1) >> t->tile_log2;
-      if (tiles + units > 0x7FFFFFFFull) return OR_ERR_SHAPE;
+      if (tiles + units > 0x7FFFFFFFull) {
+        if (m == 0) return OR_ERR_SHAPE;   // cannot happen: check_path bounds the shard length
+        break;
+      }
+      if (m == 0) ba.first = j;
       ba.tile_start[m] = (uint32_t)tiles;
       ba.b[m] = {q.grads, q.masks, q.out, q.count_out, q.shard_len, q.seed, q.base_index};
       tiles += units;
@@ -518,10 +635,135 @@ or_status batched_impl(const or_bucket* buckets, int n, int N, int k, bool bf16,
     }
     ba.n = m;
     ba.tile_start[m] = (uint32_t)tiles;
-    if (m == 0) continue;
-    if (hipError_t e = f(ba, tiles, (hipStream_t)stream, orhost::LAUNCH_ONLY)) return finish(e);
+    seen += m;
+    const int pos = (first_pending ? orhost::LAUNCH_FIRST : 0) | (seen == nonempty ? orhost::LAUNCH_LAST : 0);
+    first_pending = false;
+    if (hipError_t e = f(ba, tiles, s, pos)) return finish(e);
   }
   return OR_OK;
+}
+
+// one bucket of the separate calls on several buckets
+or_status check_stage_bucket(const or_stage_bucket& q, bool reduce, int N, int k, u64 es) {
+  const u64 L = q.shard_len;
+  if (L % 32 || L > ((u64)1 << 40)) return OR_ERR_SHAPE;
+  if (L == 0) return OR_OK;
+  if (!q.sum || !q.count) return OR_ERR_NULL;
+  if (!aligned(q.sum, 16) || !aligned(q.count, 4)) return OR_ERR_ALIGN;
+  if (ranges_overlap(q.sum, L * 4, q.count, L)) return OR_ERR_SHAPE;
+  if (reduce) {
+    if (or_status s = check_reduce(q.shards, q.masks, N, L, (int)es)) return s;
+    const u64 in_bytes = (u64)N * L * es, mask_bytes = (u64)N * (L / 8);
+    if (ranges_overlap(q.sum, L * 4, q.shards, in_bytes) || ranges_overlap(q.count, L, q.shards, in_bytes) ||
+        ranges_overlap(q.sum, L * 4, q.masks, mask_bytes) || ranges_overlap(q.count, L, q.masks, mask_bytes))
+      return OR_ERR_SHAPE;
+  } else {
+    if (L % ((u64)1 << k)) return OR_ERR_SHAPE;   // buckets hold whole blocks
+    if (check_base(k, q.base_index)) return OR_ERR_SHAPE;
+    if (!q.out) return OR_ERR_NULL;
+    if (!aligned(q.out, 16)) return OR_ERR_ALIGN;
+    if (ranges_overlap(q.out, L * es, q.count, L)) return OR_ERR_SHAPE;
+    if (ranges_overlap(q.out, L * es, q.sum, L * 4) && !((const void*)q.out == (const void*)q.sum && es == 4))
+      return OR_ERR_SHAPE;   // in place is allowed for fp32: a workgroup reads its whole tile before it writes
+  }
+  return OR_OK;
+}
+
+// or_masked_reduce_batched (reduce = true) and or_finalize_decode_batched (reduce = false)
+or_status stage_batched_impl(bool reduce, const or_stage_bucket* buckets, int n, int N, int k, bool bf16, void* stream) {
+  DisarmOnExit disarm;
+  if (n < 0) return OR_ERR_SHAPE;
+  if (!reduce && !valid_k(k)) return OR_ERR_BLOCK;
+  if (reduce && (N < 1 || N > OR_MAX_WORKERS)) return OR_ERR_WORKERS;
+  if (n == 0) return OR_OK;
+  if (!buckets) return OR_ERR_NULL;
+  const u64 es = bf16 ? 2 : 4;
+  int nonempty = 0;
+  for (int j = 0; j < n; ++j) {
+    const or_stage_bucket& q = buckets[j];
+    if (or_status s = check_stage_bucket(q, reduce, N, k, es)) return s;
+    if (q.shard_len == 0) continue;
+    ++nonempty;
+    const u64 L = q.shard_len;
+    const Span a[5] = {{reduce ? q.shards : nullptr, (u64)N * L * es, false}, {reduce ? q.masks : nullptr, (u64)N * (L / 8), false},
+                       {q.sum, L * 4, reduce}, {q.count, L, reduce}, {reduce ? nullptr : q.out, L * es, true}};
+    for (int i = 0; i < j; ++i) {
+      const or_stage_bucket& r = buckets[i];
+      const u64 M = r.shard_len;
+      const Span b[5] = {{reduce ? r.shards : nullptr, (u64)N * M * es, false}, {reduce ? r.masks : nullptr, (u64)N * (M / 8), false},
+                         {r.sum, M * 4, reduce}, {r.count, M, reduce}, {reduce ? nullptr : r.out, M * es, true}};
+      if (check_disjoint(a, b)) return OR_ERR_SHAPE;
+    }
+  }
+  if (!nonempty) return OR_OK;
+  hipStream_t s = (hipStream_t)stream;
+  const BatchPlan plan = plan_batches(nonempty);
+  const orhost::KernelTable* t = reduce ? nullptr : orhost::table_for_class(class_of(k));
+  orhost::batch_fn f = reduce ? nullptr : (bf16 ? t->finalize_decode_batched_bf16 : t->finalize_decode_batched_f32);
+  const u64 per_wg = reduce ? 256 * (16 / es) : ((u64)1 << t->tile_log2);   // entries one workgroup serves
+  int seen = 0;
+  if (!reduce && !f) {   // blocks above 2^14: one bucket after the other
+    for (int j = 0; j < n; ++j) {
+      const or_stage_bucket& q = buckets[j];
+      if (q.shard_len == 0) continue;
+      ++seen;
+      PathArgs d = {};
+      d.in = q.sum; d.count_in = q.count; d.out = q.out; d.n = d.n_pad = q.shard_len; d.seed = q.seed; d.base = q.base_index;
+      d.k = k; d.scale = scale_of(k);
+      const u64 units = q.shard_len >> t->tile_log2;
+      d.unit0 = units;
+      const int pos = (seen == 1 ? orhost::LAUNCH_FIRST : 0) | (seen == nonempty ? orhost::LAUNCH_LAST : 0);
+      if (hipError_t e = (bf16 ? t->finalize_decode_bf16 : t->finalize_decode_f32)(d, units, s, pos)) return finish(e);
+    }
+    return OR_OK;
+  }
+  for (int j = 0; seen < nonempty;) {
+    ReduceBatch rb = {};
+    ordev::BatchArgs ba = {};
+    rb.N = N;
+    ba.k = k; ba.scale = scale_of(k);
+    u64 wgs = 0;
+    int m = 0;
+    for (; j < n && m < plan.per_launch; ++j) {
+      const or_stage_bucket& q = buckets[j];
+      if (q.shard_len == 0) continue;
+      const u64 units = (q.shard_len + per_wg - 1) / per_wg;
+      if (wgs + units > 0x7FFFFFFFull) {
+        if (m == 0) return OR_ERR_SHAPE;   // cannot happen: the shard length is bounded above
+        break;
+      }
+      rb.start[m] = ba.tile_start[m] = (uint32_t)wgs;
+      rb.b[m] = {q.shards, q.masks, q.sum, q.count, q.shard_len};
+      ba.b[m] = {q.sum, q.count, q.out, nullptr, q.shard_len, q.seed, q.base_index};
+      wgs += units;
+      ++m;
+    }
+    rb.n = ba.n = m;
+    rb.start[m] = ba.tile_start[m] = (uint32_t)wgs;
+    const int pos = (seen == 0 ? orhost::LAUNCH_FIRST : 0) | (seen + m == nonempty ? orhost::LAUNCH_LAST : 0);
+    seen += m;
+    hipError_t e;
+    if (!reduce) e = f(ba, wgs, s, pos);
+    else if (bf16) e = orhost::launch_kernel(k_masked_reduce_batched<uint16_t, 8>, dim3((unsigned)wgs), dim3(256), s, pos, rb);
+    else e = orhost::launch_kernel(k_masked_reduce_batched<float, 4>, dim3((unsigned)wgs), dim3(256), s, pos, rb);
+    if (e) return finish(e);
+  }
+  return OR_OK;
+}
+
+// loss > t, exactly: missing / sent is a ratio of integers and t a binary fraction, so both sides are
+// compared as integers (no rounded quotient in between)
+bool ratio_exceeds(uint64_t missing, uint64_t sent, double t) {
+  if (t < 0.0) return true;        // a loss is never negative
+  if (t >= 1.0) return false;      // and never above 1
+  if (t == 0.0) return missing > 0;
+  int e;
+  const double fr = frexp(t, &e);                       // t = fr * 2^e, 0.5 <= fr < 1, e <= 0
+  const unsigned __int128 mant = (unsigned __int128)(uint64_t)ldexp(fr, 53);   // exact: fr has 53 bits
+  const unsigned __int128 prod = mant * sent;           // t * sent = prod / 2^(53 - e); sent < 2^48
+  const int sh = 53 - e;                                // >= 53
+  if (sh >= 120) return missing > 0;                    // t * sent < 1
+  return (unsigned __int128)missing > (prod >> sh);     // missing * 2^sh > prod  <=>  missing > floor(prod / 2^sh)
 }
 
 }  // namespace
@@ -530,7 +772,7 @@ extern "C" {
 
 uint64_t or_padded_len(uint64_t n, int block_log2) { return valid_k(block_log2) ? padded(n, block_log2) : 0; }
 size_t or_workspace_bytes(uint64_t shard_len, int block_log2) { return workspace_bytes(shard_len, block_log2); }
-int or_version(void) { return 100; }
+int or_version(void) { return 200; }
 int or_last_hip_error(void) { return g_last_hip_error; }
 
 or_status or_time_next_call(void* start_event, void* stop_event) {
@@ -636,11 +878,13 @@ or_status or_loss_decision(uint64_t received_total, int N, uint64_t shard_len, c
   if (shard_len == 0 || shard_len > UINT64_MAX / (uint64_t)N) return OR_ERR_SHAPE;
   const uint64_t sent = (uint64_t)N * shard_len;
   if (received_total > sent) return OR_ERR_SHAPE;
-  // the missing arrivals are an exact integer; one division, so that loss == 0 exactly when nothing is missing
-  const double loss = (double)(sent - received_total) / (double)sent;
-  *action_out = loss > policy->halt_loss ? OR_ACT_HALT : (loss > policy->skip_loss ? OR_ACT_SKIP : OR_ACT_APPLY);
-  *transform_on_out = (prev_transform_on || loss > policy->transform_on_loss) ? 1 : 0;
-  if (loss_out) *loss_out = loss;
+  // the missing arrivals are an exact integer, and every threshold is compared with the exact ratio
+  const uint64_t missing = sent - received_total;
+  *action_out = ratio_exceeds(missing, sent, policy->halt_loss)
+                    ? OR_ACT_HALT
+                    : (ratio_exceeds(missing, sent, policy->skip_loss) ? OR_ACT_SKIP : OR_ACT_APPLY);
+  *transform_on_out = (prev_transform_on || ratio_exceeds(missing, sent, policy->transform_on_loss)) ? 1 : 0;
+  if (loss_out) *loss_out = (double)missing / (double)sent;   // reported value only: one rounding
   return OR_OK;
 }
 
@@ -662,7 +906,24 @@ or_status or_masked_reduce_pairs(const float* sums, const uint8_t* counts, const
 
 or_status or_fused_path_batched(const or_bucket* buckets, int n_buckets, int N, int block_log2, int bf16,
                                 void* workspace, size_t workspace_bytes, void* stream) {
-  return batched_impl(buckets, n_buckets, N, block_log2, bf16 != 0, workspace, workspace_bytes, stream);
+  return path_batched_impl(true, buckets, n_buckets, N, block_log2, bf16 != 0, nullptr, workspace, workspace_bytes, stream);
+}
+or_status or_fused_path_batched_monitored(const or_bucket* buckets, int n_buckets, int N, int block_log2, int bf16,
+                                          uint64_t* totals, void* workspace, size_t workspace_bytes, void* stream) {
+  return path_batched_impl(true, buckets, n_buckets, N, block_log2, bf16 != 0, (unsigned long long*)totals, workspace,
+                           workspace_bytes, stream);
+}
+or_status or_reduce_decode_batched(const or_bucket* buckets, int n_buckets, int N, int block_log2, int bf16,
+                                   uint64_t* totals, void* workspace, size_t workspace_bytes, void* stream) {
+  return path_batched_impl(false, buckets, n_buckets, N, block_log2, bf16 != 0, (unsigned long long*)totals, workspace,
+                           workspace_bytes, stream);
+}
+or_status or_masked_reduce_batched(const or_stage_bucket* buckets, int n_buckets, int N, int bf16, void* stream) {
+  return stage_batched_impl(true, buckets, n_buckets, N, OR_MIN_LOG2, bf16 != 0, stream);
+}
+or_status or_finalize_decode_batched(const or_stage_bucket* buckets, int n_buckets, int block_log2, int bf16,
+                                     void* stream) {
+  return stage_batched_impl(false, buckets, n_buckets, 1, block_log2, bf16 != 0, stream);
 }
 
 }  // extern "C"

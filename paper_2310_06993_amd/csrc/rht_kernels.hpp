@@ -37,6 +37,7 @@ struct PathArgs {
   uint8_t* count_out;      // may be null
   float* mean_out;         // fused without decode: mean in the encoded domain, fp32
   const u64* sign_tab;     // fused, blocks above 2^14: sign bits of the shard's entries, 64 per word (see k_fused_pairs)
+  unsigned long long* total_out;   // may be null: receives the number of (worker, entry) arrivals (Sec. 3.4 loss monitoring)
   u64 n;                   // valid entries of the input (encode) / output (decode)
   u64 n_pad;               // padded length = vector length on the encoded side; shard_len for reduce/fused
   u64 seed;
@@ -181,12 +182,11 @@ __device__ __forceinline__ void load_mean_tile(const PathArgs& a, u64 tile, int 
 
 // Sec. 3.3 / Sec. 4 decode: out = D B^(-1/2) H mean, first n entries kept.
 template <int K, class Out, bool FINALIZE, bool FULL, bool MASKED = false>
-__global__ __launch_bounds__(Geo<K>::THREADS) void k_decode(PathArgs a) {
+__device__ __forceinline__ void decode_tile(const PathArgs& a, u64 unit) {
   constexpr int T = Geo<K>::T, R = Geo<K>::R;
   static_assert(Geo<K>::PARTS == 1, "larger blocks use k_decode_block");
   __shared__ float xbuf[Geo<K>::Q > 0 ? T : 1];
   const int wave = wave_id(), lane = lane_id(), kt = tile_bits<K>(a.k);
-  const u64 unit = a.unit0 + blockIdx.x;
   float v[R];
   load_mean_tile<K, FINALIZE, FULL, MASKED>(a, unit, wave, lane, v);
   transform<K, false>(v, xbuf, wave, lane, kt);
@@ -197,6 +197,10 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_decode(PathArgs a) {
   for (int r = 0; r < R; ++r) v[r] *= c;
   apply_signs(v, sg);
   store_tile<K, false, FULL>((Out*)a.out, unit * T, a.n, wave, lane, v);
+}
+template <int K, class Out, bool FINALIZE, bool FULL, bool MASKED = false>
+__global__ __launch_bounds__(Geo<K>::THREADS) void k_decode(PathArgs a) {
+  decode_tile<K, Out, FINALIZE, FULL, MASKED>(a, a.unit0 + blockIdx.x);
 }
 
 // The same for blocks above 2^14 (see k_encode_block).  The input holds whole blocks; FULL = false: the
@@ -250,6 +254,20 @@ __device__ __forceinline__ int count_of(const uint32_t (&cntp)[NR / 4], int full
   return (int)((cntp[r >> 2] >> (8 * (r & 3))) & 0xFFu) + full;
 }
 
+// Sec. 3.4 loss monitoring: adds this wavefront's number of arrivals (its `full` workers count for all of its
+// 64 * NR entries, the rest sit in the packed bytes) to *total with one atomic.
+template <int NR>
+__device__ __forceinline__ void add_arrivals(unsigned long long* total, const uint32_t (&cntp)[NR / 4], int full) {
+  uint32_t mine = 0;
+#pragma unroll
+  for (int r = 0; r < NR / 4; ++r) mine = __builtin_amdgcn_sad_u8(cntp[r], 0u, mine);
+  unsigned long long w = mine;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) w += __shfl_xor(w, o, 64);
+  w += (unsigned long long)full * (64u * NR);
+  if (lane_id() == 0 && w) atomicAdd(total, w);
+}
+
 template <int K, bool FULL>
 __device__ __forceinline__ void store_counts(uint8_t* count_out, u64 e0, u64 limit, int wave, int lane,
                                              const uint32_t (&cntp)[Geo<K>::R / 4], int full) {
@@ -285,13 +303,13 @@ __device__ __forceinline__ void finalize_mean(float (&acc)[NR], const uint32_t (
 // Aggregation of N encoded shards (Sec. 3.1.1), mean over what arrived, decode (Sec. 3.3).  K <= 14.
 // The next worker's tile is in flight while the current one is accumulated.
 template <int K, class Wire, class Out>
-__global__ __launch_bounds__(Geo<K>::THREADS) void k_reduce_decode(PathArgs a) {
+__device__ __forceinline__ void reduce_decode_tile(const PathArgs& a, u64 unit) {
   constexpr int T = Geo<K>::T, R = Geo<K>::R;
   constexpr bool FULL = kShardTilesFull<K>;
   static_assert(Geo<K>::PARTS == 1, "blocks above 2^14 go through sum/count in memory");
   __shared__ float xbuf[Geo<K>::Q > 0 ? T : 1];
   const int wave = wave_id(), lane = lane_id(), kt = tile_bits<K>(a.k);
-  const u64 unit = blockIdx.x, L = a.n_pad, e0 = unit * T;
+  const u64 L = a.n_pad, e0 = unit * T;
   const Wire* shards = (const Wire*)a.in;
   float acc[R], va[R], vb[R];
   uint32_t ma, mb = 0, cnt[R / 4];
@@ -319,6 +337,7 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_reduce_decode(PathArgs a) {
     }
   }
   store_counts<K, FULL>(a.count_out, e0, L, wave, lane, cnt, full);
+  if (a.total_out) add_arrivals<R>(a.total_out, cnt, full);
   finalize_mean(acc, cnt, full, 1.0f);
   transform<K, false>(acc, xbuf, wave, lane, kt);
   const float c = a.scale * lane_sigma(lane, kt < 6 ? kt : 6);
@@ -328,6 +347,10 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_reduce_decode(PathArgs a) {
   for (int r = 0; r < R; ++r) acc[r] *= c;
   apply_signs(acc, sg);
   store_tile<K, false, FULL, true>((Out*)a.out, e0, L, wave, lane, acc);
+}
+template <int K, class Wire, class Out>
+__global__ __launch_bounds__(Geo<K>::THREADS) void k_reduce_decode(PathArgs a) {
+  reduce_decode_tile<K, Wire, Out>(a, blockIdx.x);
 }
 
 // The whole path for one shard held by one node: the raw slices of N workers are encoded, the
@@ -425,6 +448,7 @@ __device__ __forceinline__ void fused_tile(const PathArgs& a, u64 unit) {
   }
   __builtin_amdgcn_sched_barrier(0);
   store_counts<K, FULL>(a.count_out, e0, L, wave, lane, cnt, full);
+  if (a.total_out) add_arrivals<R>(a.total_out, cnt, full);
   finalize_mean(acc, cnt, full, sigma * (scale_first ? 1.0f : a.scale));
   __builtin_amdgcn_sched_barrier(0);
   if constexpr (TRANSP) {
@@ -548,6 +572,10 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_fused_pairs(PathArgs a) {
   }
   __builtin_amdgcn_sched_barrier(0);
   const float post = sigma * (scale_first ? 1.0f : a.scale);
+  if (a.total_out) {
+    add_arrivals<R>(a.total_out, cnt_lo, full_lo);
+    add_arrivals<R>(a.total_out, cnt_hi, full_hi);
+  }
   store_counts<K, true>(a.count_out, e_lo, L, wave, lane, cnt_lo, full_lo);
   finalize_mean(acc_lo, cnt_lo, full_lo, post);
   if constexpr (HP == 2) store_tile<K, true, true>(a.mean_out, e_lo, L, wave, lane, acc_lo);
@@ -587,8 +615,8 @@ __global__ __launch_bounds__(Geo<K>::THREADS) void k_fused_pairs(PathArgs a) {
 // in the kernel arguments; workgroup x serves tile x - tile_start[j] of bucket j.
 constexpr int kMaxBatch = 64;   // 64 descriptors keep BatchArgs under the 4 KB of kernel arguments
 struct BucketArgs {
-  const void* in;
-  const uint32_t* masks;
+  const void* in;          // raw slices / encoded shards; finalize+decode: the fp32 sums
+  const void* aux;         // received masks [N][L/32]; finalize+decode: the uint8 counts
   void* out;
   uint8_t* count_out;
   u64 shard_len, seed, base;
@@ -596,23 +624,49 @@ struct BucketArgs {
 struct BatchArgs {
   int n, N, k;
   float scale;
+  unsigned long long* totals;   // may be null: totals[first + j] receives bucket j's number of arrivals
+  int first;
   uint32_t tile_start[kMaxBatch + 1];
   BucketArgs b[kMaxBatch];
 };
 
 static_assert(sizeof(BatchArgs) <= 4096, "kernel arguments are limited to 4 KB");
 
-template <int K, class In, bool PREFETCH>
-__global__ __launch_bounds__(Geo<K>::THREADS) __attribute__((amdgpu_waves_per_eu(Geo<K>::R == 32 ? 4 : 1)))
-void k_fused_batched(BatchArgs ba) {
+// the bucket that workgroup x serves, as the arguments of a single-bucket call; returns the tile inside it
+__device__ __forceinline__ u64 bucket_of(const BatchArgs& ba, PathArgs& a) {
   const uint32_t x = blockIdx.x;
   int j = 0;
   while (j + 1 < ba.n && ba.tile_start[j + 1] <= x) ++j;
-  PathArgs a = {};
-  a.in = ba.b[j].in; a.masks = ba.b[j].masks; a.out = ba.b[j].out; a.count_out = ba.b[j].count_out;
+  a = PathArgs{};
+  a.in = ba.b[j].in; a.masks = (const uint32_t*)ba.b[j].aux; a.count_in = (const uint8_t*)ba.b[j].aux;
+  a.out = ba.b[j].out; a.count_out = ba.b[j].count_out;
   a.n = a.n_pad = ba.b[j].shard_len; a.seed = ba.b[j].seed; a.base = ba.b[j].base;
   a.N = ba.N; a.k = ba.k; a.scale = ba.scale;
-  fused_tile<K, In, PREFETCH>(a, x - ba.tile_start[j]);
+  a.total_out = ba.totals ? ba.totals + ba.first + j : nullptr;
+  return x - ba.tile_start[j];
+}
+
+template <int K, class In, bool PREFETCH>
+__global__ __launch_bounds__(Geo<K>::THREADS) __attribute__((amdgpu_waves_per_eu(Geo<K>::R == 32 ? 4 : 1)))
+void k_fused_batched(BatchArgs ba) {
+  PathArgs a;
+  const u64 unit = bucket_of(ba, a);
+  fused_tile<K, In, PREFETCH>(a, unit);
+}
+
+// The three-call path on several buckets: aggregation + mean + decode of encoded shards, and mean + decode of
+// (sum, count) pairs; every bucket holds whole blocks.
+template <int K, class Wire>
+__global__ __launch_bounds__(Geo<K>::THREADS) void k_reduce_decode_batched(BatchArgs ba) {
+  PathArgs a;
+  const u64 unit = bucket_of(ba, a);
+  reduce_decode_tile<K, Wire, Wire>(a, unit);
+}
+template <int K, class Out>
+__global__ __launch_bounds__(Geo<K>::THREADS) void k_finalize_decode_batched(BatchArgs ba) {
+  PathArgs a;
+  const u64 unit = bucket_of(ba, a);
+  decode_tile<K, Out, true, kShardTilesFull<K>, false>(a, unit);
 }
 
 }  // namespace ordev

@@ -100,10 +100,19 @@ def test_loss_decision_matches_the_oracle(orc):
                 act, on, loss = b.or_loss_decision(recv, N, L, pol, prev)
                 eact, eon, eloss = orc.loss_decision(recv, N, L, ton, skip, halt, prev)
                 assert abs(loss - eloss) <= 1e-15
-                # a loss within one rounding of a threshold may fall on either side in double arithmetic
-                near = any(abs(eloss - t) <= 1e-15 for t in (ton, skip, halt))
-                if not near:
-                    assert (act, bool(on)) == (eact, eon), (recv, N, L, prev, ton, skip, halt)
+                assert (act, bool(on)) == (eact, eon), (recv, N, L, prev, ton, skip, halt)
+    # losses that sit exactly on a decimal fraction whose double is a hair above or below it: the comparison
+    # is between the exact ratio and the exact value of the double (0.1 and 0.2 are above 1/10 and 1/5,
+    # 0.3 is below 3/10), never between two rounded doubles
+    for recv, N, L in ((9000, 10, 1000), (8000, 10, 1000), (7000, 10, 1000), (8999, 10, 1000), (7001, 10, 1000),
+                       (3 * (1 << 40) * 7 // 10, 3, 1 << 40), (255 * 10 ** 9 * 9 // 10, 255, 10 ** 9)):
+        for ton, skip, halt in ((0.1, 0.2, 0.3), (0.3, 0.1, 0.2), (0.1 + 2 ** -56, 0.3 - 2 ** -55, 0.7)):
+            pol = b.or_loss_policy(ton, skip, halt)
+            act, on, _ = b.or_loss_decision(recv, N, L, pol, False)
+            eact, eon, _ = orc.loss_decision(recv, N, L, ton, skip, halt, False)
+            assert (act, bool(on)) == (eact, eon), (recv, N, L, ton, skip, halt)
+    assert b.or_loss_decision(7000, 10, 1000, b.or_loss_policy(0.3, 2.0, 2.0), False)[1] == 1   # 3/10 > double(0.3)
+    assert b.or_loss_decision(9000, 10, 1000, b.or_loss_policy(0.1, 2.0, 2.0), False)[1] == 0   # 1/10 < double(0.1)
     pol = b.or_loss_policy(0.02, 0.05, 0.5)
     for bad, code in (((9, 1, 8), 4), ((0, 0, 8), 3), ((0, 256, 8), 3), ((0, 1, 0), 4)):
         with pytest.raises(b.OptiReduceError) as e:
@@ -111,3 +120,61 @@ def test_loss_decision_matches_the_oracle(orc):
         assert e.value.status == code
     with pytest.raises(b.OptiReduceError):
         b.or_loss_decision(1, 1, 8, b.or_loss_policy(float("nan"), 0.0, 0.0), False)
+
+
+def test_batched_argument_checks(lib):
+    """The batched entry points validate every bucket on the host before anything is enqueued (fake addresses,
+    never touched)."""
+    from paper_2310_06993_amd import binding as b
+    p, i32 = ctypes.c_void_p, ctypes.c_int
+    fb = lib.or_fused_path_batched_monitored
+    fb.argtypes = [p, i32, i32, i32, i32, p, p, ctypes.c_size_t, p]
+    rd = lib.or_reduce_decode_batched
+    rd.argtypes = fb.argtypes
+    L = 4096
+    A = 1 << 30
+
+    def bucket(j, **kw):
+        d = dict(grads=A + j * (1 << 24), masks=A + j * (1 << 24) + (1 << 22), out=A + j * (1 << 24) + (1 << 23),
+                 count_out=None, shard_len=L, seed=1, base_index=0)
+        d.update(kw)
+        return b.or_bucket(**d)
+
+    two = (b.or_bucket * 2)(bucket(0), bucket(1))
+    assert fb(None, 0, 4, 12, 0, None, None, 0, None) == 0
+    assert fb(None, 2, 4, 12, 0, None, None, 0, None) == 1
+    assert fb(two, -1, 4, 12, 0, None, None, 0, None) == 4
+    assert fb(two, 2, 0, 12, 0, None, None, 0, None) == 3
+    assert fb(two, 2, 4, 17, 0, None, None, 0, None) == 2
+    assert fb(two, 2, 4, 12, 0, 4, None, 0, None) == 5                       # totals not 8-byte aligned
+    assert rd(two, 2, 4, 13, 0, None, None, 0, None) == 4                    # 4096 is not a whole 2^13 block
+    clash = (b.or_bucket * 2)(bucket(0), bucket(1, out=two[0].grads + 64))   # writes into bucket 0's input
+    assert fb(clash, 2, 4, 12, 0, None, None, 0, None) == 4
+    assert rd(clash, 2, 4, 12, 0, None, None, 0, None) == 4
+    big = (b.or_bucket * 1)(bucket(0, shard_len=1 << 16))
+    assert fb(big, 1, 2, 16, 1, None, None, 0, None) == 6                    # blocks above 2^14 need the workspace
+    mr = lib.or_masked_reduce_batched
+    mr.argtypes = [p, i32, i32, i32, p]
+    fd = lib.or_finalize_decode_batched
+    fd.argtypes = [p, i32, i32, i32, p]
+
+    def stage(j, **kw):
+        base = A + j * (1 << 24)
+        d = dict(shards=base, masks=base + (1 << 22), sum=base + (1 << 23), count=base + (1 << 23) + (1 << 21),
+                 out=base + (1 << 23) + (1 << 22), shard_len=L, seed=1, base_index=0)
+        d.update(kw)
+        return b.or_stage_bucket(**d)
+
+    st = (b.or_stage_bucket * 2)(stage(0), stage(1))
+    assert mr(None, 0, 4, 0, None) == 0 and mr(None, 1, 4, 0, None) == 1
+    assert mr(st, 2, 0, 0, None) == 3
+    assert fd(st, 2, 4, 0, None) == 2
+    assert fd(st, 2, 13, 0, None) == 4
+    bad = (b.or_stage_bucket * 2)(stage(0), stage(1, sum=None))
+    assert mr(bad, 2, 4, 0, None) == 1 and fd(bad, 2, 12, 0, None) == 1
+    bad = (b.or_stage_bucket * 2)(stage(0), stage(1, sum=st[0].sum + 16))
+    assert mr(bad, 2, 4, 0, None) == 4
+    bad = (b.or_stage_bucket * 1)(stage(0, shard_len=48))
+    assert mr(bad, 1, 4, 0, None) == 4
+    bad = (b.or_stage_bucket * 1)(stage(0, base_index=64))
+    assert fd(bad, 1, 12, 0, None) == 4

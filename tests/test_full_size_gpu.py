@@ -40,11 +40,11 @@ def _fused(b, cfg, g, m, L, base, out, cnt):
     torch.cuda.synchronize()
 
 
-def _check_sampled_blocks(orc, cfg, g, m, out, cnt, L, base, nsamples, seed):
+def _check_sampled_blocks(orc, cfg, g, m, out, cnt, L, base, nsamples, seed, extra=()):
     B, k = cfg.block, cfg.block_log2
     nblocks = L // B
     rng = np.random.default_rng(seed)
-    picks = sorted(set([0, nblocks - 1] + rng.integers(0, nblocks, nsamples).tolist()))
+    picks = sorted(set([0, nblocks - 1] + rng.integers(0, nblocks, nsamples).tolist() + [int(x) for x in extra]))
     worst = 0.0
     for blk in picks:
         gs = to_np(g[:, blk * B:(blk + 1) * B].contiguous())
@@ -58,7 +58,7 @@ def _check_sampled_blocks(orc, cfg, g, m, out, cnt, L, base, nsamples, seed):
     return worst
 
 
-def _run_config(b, orc, cfg, shard, entries=None, nsamples=6):
+def _run_config(b, orc, cfg, shard, entries=None, nsamples=6, extra=()):
     from paper_2310_06993_amd import workloads as wl
     N, L = cfg.workers, cfg.shard_len(entries)
     g = wl.make_grads(cfg, dev(), shard=shard, entries=entries)
@@ -72,7 +72,7 @@ def _run_config(b, orc, cfg, shard, entries=None, nsamples=6):
     assert int(cnt.min()) >= 1                       # the owner's copy is always there
     lost = 1.0 - float(cnt.float().mean()) / N
     assert 0.2 * cfg.loss < lost * N / (N - 1) < 3.0 * cfg.loss, (cfg.name, lost)
-    worst = _check_sampled_blocks(orc, cfg, g, m, out, cnt, L, base, nsamples, seed=shard + 1)
+    worst = _check_sampled_blocks(orc, cfg, g, m, out, cnt, L, base, nsamples, seed=shard + 1, extra=extra)
     # all arrived + small integers: the exact mean, everywhere
     del g
     gi = torch.randint(-4, 5, (N, L), device=dev(), dtype=torch.int8,
@@ -149,7 +149,14 @@ def test_llama_8b_sized(b, orc):
     from paper_2310_06993_amd import workloads as wl
     cfg = wl.CONFIGS["llama_8b"]
     assert cfg.shard_len() == 1_003_814_912 and cfg.entries > 2 ** 32
-    _run_config(b, orc, cfg, shard=7, nsamples=3)     # last shard: base index beyond 2^32, holds the pad
+    nblocks = cfg.shard_len() >> cfg.block_log2
+    assert nblocks == 15_317
+    # The kernels for blocks above 2^14 place the workgroups of a block by its index modulo 8 (one L2 each) and
+    # round the grid up to whole groups of 8 blocks: sample every residue in the middle of the shard, every block
+    # of the last, partial group (15,317 = 8 * 1914 + 5) and the whole group before it.
+    mid = 8 * 957
+    extra = list(range(mid, mid + 8)) + list(range(nblocks - 5 - 8, nblocks))
+    _run_config(b, orc, cfg, shard=7, nsamples=3, extra=extra)     # last shard: base index beyond 2^32, holds the pad
 
 
 def test_llama_8b_full_gradient_encode_and_decode(b, orc):

@@ -14,7 +14,8 @@ pytestmark = pytest.mark.gpu
 @pytest.mark.parametrize("loss", [0.01, 0.05, 0.10])
 def test_tail_drops_with_and_without_transform(loss):
     import paper_2310_06993_amd.binding as b
-    from paper_2310_06993_amd import workloads as wl
+    import oracle
+    from _util import to_np, rel_l2, TOL
     N, k = 8, 12
     L = 64 << k
     gen = torch.Generator(device=dev()).manual_seed(int(loss * 1000))
@@ -34,6 +35,12 @@ def test_tail_drops_with_and_without_transform(loss):
     b.or_masked_reduce(g, m, N, L, total, cnt)
     plain = torch.empty(L, device=dev())
     b.or_finalize(total, cnt, L, plain)
+    # both routes against the oracle first: the figures below are then properties of the method, not of this build
+    gh, mh = to_np(g), to_np(m)
+    want, wcnt = oracle.fused_path(gh, mh, k, 7, 0)
+    assert np.array_equal(to_np(cnt), wcnt) and rel_l2(to_np(out), want) <= TOL["f32"]
+    wsum, wcnt2 = oracle.masked_reduce(gh, mh)
+    assert np.array_equal(wcnt2, wcnt) and rel_l2(to_np(plain), oracle.finalize(wsum, wcnt2)) <= TOL["f32"]
     err_ht = (out.double() - truth).abs()
     err_plain = (plain.double() - truth).abs()
     lost = 1.0 - float(cnt.float().mean()) / N
