@@ -141,6 +141,21 @@ or_status or_fused_path_bf16(const uint16_t* grads, const uint32_t* masks, int N
                              int block_log2, uint64_t seed, uint64_t base_index, uint16_t* out, uint8_t* count_out,
                              void* workspace, size_t workspace_bytes, void* stream);
 
+/* or_fused_path_bf16_static: or_fused_path_bf16 for callers that cannot allocate device memory or must not
+ * pass a workspace (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc).
+ * The workspace of the kernels for block_log2 > 14 is a static array in device memory inside the library,
+ * (5 * OR_STATIC_MAX_SHARD_LEN bytes, 20 MiB, held by every GPU the library runs on until the process ends);
+ * for block_log2 <= 14 no workspace is used.  Same arguments, checks, kernels and results as
+ * or_fused_path_bf16 otherwise.  block_log2 > 14 with shard_len > OR_STATIC_MAX_SHARD_LEN is rejected
+ * with OR_ERR_WORKSPACE.  The call allocates nothing; its first call on a device looks the array's address
+ * up (make that call outside a graph capture).  Every call on a GPU uses that GPU's one array: calls with
+ * block_log2 > 14 that may overlap in time on one GPU (different streams, several host threads) race on
+ * it -- keep them on one stream or order them with events. */
+#define OR_STATIC_MAX_SHARD_LEN 4194304ull
+or_status or_fused_path_bf16_static(const uint16_t* grads, const uint32_t* masks, int N, uint64_t shard_len,
+                                    int block_log2, uint64_t seed, uint64_t base_index, uint16_t* out,
+                                    uint8_t* count_out, void* stream);
+
 /* ---- around the path: transform off, second-stage loss, loss monitoring, two-level aggregation ----
  *
  * or_finalize: the "averages" of Sec. 3.1.1 alone, mean = sum / count and 0 where count is 0 -- with

@@ -44,6 +44,7 @@ _SIGS = {
     "or_reduce_decode_bf16": (_int, [_p, _p, _int, _u64, _int, _u64, _u64, _p, _p, _p, _sz, _p]),
     "or_fused_path": (_int, [_p, _p, _int, _u64, _int, _u64, _u64, _p, _p, _p, _sz, _p]),
     "or_fused_path_bf16": (_int, [_p, _p, _int, _u64, _int, _u64, _u64, _p, _p, _p, _sz, _p]),
+    "or_fused_path_bf16_static": (_int, [_p, _p, _int, _u64, _int, _u64, _u64, _p, _p, _p]),
     "or_fused_path_batched": (_int, [_p, _int, _int, _int, _int, _p, _sz, _p]),
     "or_fused_path_batched_monitored": (_int, [_p, _int, _int, _int, _int, _p, _p, _sz, _p]),
     "or_reduce_decode_batched": (_int, [_p, _int, _int, _int, _int, _p, _p, _sz, _p]),
@@ -206,6 +207,15 @@ def or_fused_path_bf16(grads, masks, N, shard_len, block_log2, seed, base_index,
     w, wb = _ws(workspace)
     _check(lib.or_fused_path_bf16(_ptr(grads), _ptr(masks), N, shard_len, block_log2, seed, base_index, _ptr(out),
                                   _ptr(count_out), w, wb, _stream(stream)), "or_fused_path_bf16")
+
+
+OR_STATIC_MAX_SHARD_LEN = 4194304
+
+
+def or_fused_path_bf16_static(grads, masks, N, shard_len, block_log2, seed, base_index, out, count_out=None,
+                              stream=None):
+    _check(lib.or_fused_path_bf16_static(_ptr(grads), _ptr(masks), N, shard_len, block_log2, seed, base_index,
+                                         _ptr(out), _ptr(count_out), _stream(stream)), "or_fused_path_bf16_static")
 
 
 def make_buckets(items):

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <math.h>
+#include <mutex>
 
 #include "../../include/optireduce.h"
 #include "launch_table.hpp"
@@ -751,6 +752,37 @@ or_status stage_batched_impl(bool reduce, const or_stage_bucket* buckets, int n,
   return OR_OK;
 }
 
+// ------------------------------------------------------------------ scratch for callers that cannot allocate
+// or_fused_path_bf16_static: the workspace of the kernels for blocks above 2^14 lives in this array instead of
+// caller memory.  Each GPU holds its own copy at its own address; host code never uses the array's name as an
+// address, only the pointer that hipGetSymbolAddress returned for the device that is current.
+constexpr u64 kStaticMaxShard = OR_STATIC_MAX_SHARD_LEN;
+constexpr size_t kScratchBytes = ((kStaticMaxShard * 4 + 255) / 256 * 256) + ((kStaticMaxShard + 255) / 256 * 256);
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// the scratch array's address on the current device (looked up once per device), or null with *err set
+void* scratch_of_current_device(hipError_t* err) {
+  int dev = -1;
+  *err = hipGetDevice(&dev);
+  if (*err != hipSuccess) return nullptr;
+  if (dev < 0 || dev >= kMaxDevices) {
+    *err = hipErrorInvalidDevice;
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> hold(g_scratch_lock);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (*err != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
+
 // loss > t, exactly: missing / sent is a ratio of integers and t a binary fraction, so both sides are
 // compared as integers (no rounded quotient in between)
 bool ratio_exceeds(uint64_t missing, uint64_t sent, double t) {
@@ -859,6 +891,22 @@ or_status or_fused_path_bf16(const uint16_t* grads, const uint32_t* masks, int N
                              void* workspace, size_t workspace_bytes, void* stream) {
   return path_impl<uint16_t>(true, grads, masks, N, shard_len, block_log2, seed, base_index, out, count_out, workspace,
                              workspace_bytes, stream, true);
+}
+
+or_status or_fused_path_bf16_static(const uint16_t* grads, const uint32_t* masks, int N, uint64_t shard_len,
+                                    int block_log2, uint64_t seed, uint64_t base_index, uint16_t* out,
+                                    uint8_t* count_out, void* stream) {
+  DisarmOnExit disarm;
+  const size_t need = workspace_bytes(shard_len, block_log2);
+  if (need && shard_len > kStaticMaxShard) return OR_ERR_WORKSPACE;   // beyond what the static scratch holds
+  void* ws = nullptr;
+  if (need) {
+    hipError_t e;
+    ws = scratch_of_current_device(&e);
+    if (!ws) return finish(e);
+  }
+  if (or_status s = check_path(grads, masks, N, shard_len, block_log2, base_index, out, count_out, ws, need, 2)) return s;
+  return run_path<uint16_t>(true, grads, masks, N, shard_len, block_log2, seed, base_index, out, count_out, ws, stream, true);
 }
 
 or_status or_finalize(const float* sum, const uint8_t* count, uint64_t shard_len, float* mean_out, void* stream) {
