@@ -1,5 +1,8 @@
 // One block-size class of kernels (compile with -DOR_K=0, 11, 12, ... 16).
 #include "launch_table.hpp"
+#if OR_K > 14
+#include "rht_fused_wide.hpp"
+#endif
 
 #ifndef OR_K
 #error "compile with -DOR_K=<class>"
@@ -115,7 +118,7 @@ OR_FUSED_LAUNCHER(fusb_bf16, BatchArgs, k_fused_batched)
     return launch_kernel(kernel, dim3((unsigned)grid), dim3(G::THREADS), s, pos, a);         \
   }
 OR_PAIR_LAUNCHER(fus_f32, (k_fused_pairs<K, float>))
-OR_PAIR_LAUNCHER(fus_bf16, (k_fused_pairs<K, bf16_t>))
+OR_PAIR_LAUNCHER(fus_bf16, (k_fused_wide<K>))
 #endif
 }  // namespace
 

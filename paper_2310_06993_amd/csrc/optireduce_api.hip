@@ -188,6 +188,34 @@ __global__ __launch_bounds__(256) void k_sign_table(uint4* __restrict__ tab, u64
   tab[c] = make_uint4(w.a, w.b, w.c, w.d);
 }
 
+// The same signs in the order the bf16 kernels for blocks above 2^14 hold their registers: word w belongs to
+// the 1024-entry slice w / 16 and its register r = w % 16; bit l is the sign of entry
+// slice * 1024 + (r / 8) * 512 + l * 8 + (r % 8), counted from `first_entry` (a multiple of 512).
+// Also clears the `n_flag_words` words of the pair hand-over that the fused kernel for 2^16 blocks uses.
+__global__ __launch_bounds__(256) void k_sign_table_strided(u64* __restrict__ tab, u64 seed, u64 first_entry, u64 n_words,
+                                                            unsigned* __restrict__ flags, u64 n_flag_words) {
+  const u64 w = (u64)blockIdx.x * 256 + threadIdx.x;
+  if (w < n_flag_words) flags[w] = 0;
+  if (w >= n_words) return;
+  const u64 slice = w >> 4;
+  const int r = (int)(w & 15), j = r & 7;
+  const u64 ctr0 = (first_entry + slice * 1024 + (u64)(r >> 3) * 512) >> 7;   // four counters cover the run of 512
+  u64 bits = 0;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const u64 ctr = ctr0 + q;
+    const ordev::u32x4 o =
+        ordev::philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), 0u, 0u, (uint32_t)seed, (uint32_t)(seed >> 32));
+    const uint32_t word[4] = {o.a, o.b, o.c, o.d};
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int s8 = 0; s8 < 4; ++s8)   // entry q*128 + t*32 + s8*8 + j of the run sits on lane q*16 + t*4 + s8
+        bits |= (u64)((word[t] >> (j + 8 * s8)) & 1u) << (q * 16 + t * 4 + s8);
+  }
+  tab[w] = bits;
+}
+
 // Sec. 3.4 loss monitoring: total of the received counts of a shard (16 counts per lane, byte sums
 // with v_sad_u8, one 64-bit atomic per wavefront)
 __global__ __launch_bounds__(256) void k_received_total(const uint8_t* __restrict__ count, u64 L,
@@ -430,6 +458,21 @@ or_status run_path(bool fused, const T* in, const uint32_t* masks, int N, u64 L,
   d.out = out; d.n = L; d.n_pad = L; d.seed = seed; d.base = base; d.k = k; d.scale = a.scale;
   d.in = ws_f32;
   d.unit0 = units;   // shards hold whole blocks: no tile of the decode needs bounds checks
+  if (fused && bf16) {
+    // bf16: one kernel does everything.  Workspace: [hand-over slots of the workgroup pairs, 4 L bytes, k = 16 only]
+    // [sign table in register order, L/8 bytes][pair flags, 8 bytes a block]
+    const u64 words = L >> 6, nflags = k == 16 ? 2 * (L >> 16) : 0;
+    unsigned* flags = (unsigned*)(ws_cnt + (L / 8 + 255) / 256 * 256);
+    const u64 blocks = ((words > nflags ? words : nflags) + 255) / 256;
+    if (blocks > 0x7FFFFFFFull) return OR_ERR_SHAPE;
+    if (hipError_t e = orhost::launch_kernel(k_sign_table_strided, dim3((unsigned)blocks), dim3(256), s, first, (u64*)ws_cnt,
+                                             seed, base, words, flags, nflags))
+      return finish(e);
+    a.sign_tab = (const u64*)ws_cnt;
+    a.mean_out = ws_f32;
+    a.count_in = (const uint8_t*)flags;
+    return finish(t->fused_bf16(a, units, s, last));
+  }
   if (fused) {
     // the sign table takes the part of the workspace that the unfused path uses for counts (L/8 of its L bytes)
     const u64 counters = L >> 7;
@@ -439,11 +482,11 @@ or_status run_path(bool fused, const T* in, const uint32_t* masks, int N, u64 L,
       return finish(e);
     a.sign_tab = (const u64*)ws_cnt;
     if (k == 15)   // two tiles per block: the fused kernel decodes as well
-      return finish((bf16 ? t->fused_bf16 : t->fused_f32)(a, units, s, last));
+      return finish(t->fused_f32(a, units, s, last));
     a.mean_out = ws_f32;
     a.out = nullptr;
-    if (hipError_t e = (bf16 ? t->fused_bf16 : t->fused_f32)(a, units, s, 0)) return finish(e);
-    return finish((bf16 ? t->decode_bf16 : t->decode_f32)(d, units, s, last));
+    if (hipError_t e = t->fused_f32(a, units, s, 0)) return finish(e);
+    return finish(t->decode_f32(d, units, s, last));
   }
   uint8_t* cnt = count_out ? count_out : ws_cnt;
   constexpr int VEC = 16 / sizeof(T);
