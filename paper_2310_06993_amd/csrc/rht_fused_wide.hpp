@@ -143,43 +143,6 @@ __global__ __launch_bounds__(1024) void k_fused_wide(PathArgs a) {
     const uint32_t* row = a.masks + (u64)i * mrow;
     const int nxt = i + 1 < a.N ? i + 1 : i;
     float A[R], C[R];
-#ifdef OR_X_MFMA_FRONT
-    // timing experiment only (wrong results, same memory accesses): what a matrix-core front end would cost
-    {
-      typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
-      typedef float f4 __attribute__((ext_vector_type(4)));
-      const bf8 hmat = __builtin_bit_cast(bf8, u32x4v{0x3F803F80u, 0xBF803F80u, 0x3F80BF80u, 0xBF80BF80u ^ (uint32_t)lane});
-      u32x4v* ps[8] = {&p0[0], &p0[1], &p1[0], &p1[1], &p2[0], &p2[1], &p3[0], &p3[1]};
-      const uint32_t sb = mw * 0x9E3779B9u;
-#pragma unroll
-      for (int c = 0; c < (HP == 2 ? 8 : 4); ++c) {
-        u32x4v x = *ps[HP == 2 ? c : (c < 2 ? c : c + 2)];
-        const uint32_t byte = (sb >> (4 * c)) & 0xFFu;
-#pragma unroll
-        for (int d = 0; d < 4; ++d) x[d] ^= (byte * (0x40008000u >> (2 * d))) & 0x80008000u;
-        f4 acc4 = {0, 0, 0, 0};
-        acc4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hmat, __builtin_bit_cast(bf8, x), acc4, 0, 0, 0);
-        if (HP == 2) {
-          float* dst = c < 4 ? &A[4 * c] : &C[4 * (c - 4)];
-          dst[0] = acc4[0]; dst[1] = acc4[1]; dst[2] = acc4[2]; dst[3] = acc4[3];
-        } else {
-          float* dst = c < 2 ? &A[8 * c] : &C[8 * (c - 2)];
-          dst[0] = acc4[0]; dst[1] = acc4[1]; dst[2] = acc4[2]; dst[3] = acc4[3];
-          acc4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hmat, __builtin_bit_cast(bf8, x), f4{1, 0, 0, 0}, 0, 0, 0);
-          dst[4] = acc4[0]; dst[5] = acc4[1]; dst[6] = acc4[2]; dst[7] = acc4[3];
-        }
-      }
-    }
-    OR_PIN16(A);
-    OR_PIN16(C);
-    const bool mine_clean = all_arrived(mw);
-    if (lane == 0) s_clean[wave] = mine_clean ? 1u : 0u;
-    request(nxt, 0, p0);
-    if constexpr (HP == 2) request(nxt, 1, p1);
-    mw = my_words[(u64)nxt * mrow];
-    request(nxt, HP, p2);
-    if constexpr (HP == 2) request(nxt, HP + 1, p3);
-#else
     add_signed(A, p0, 0, false, true);
     if constexpr (HP == 2) add_signed(A, p1, 1, part_coef(h, 1) < 0.0f, false);
     OR_PIN16(A);
@@ -197,7 +160,6 @@ __global__ __launch_bounds__(1024) void k_fused_wide(PathArgs a) {
       C[r] = A[r] - C[r];
       A[r] = s;
     }
-#endif
     transform_transposed<K>(A, tbuf[flip], tbuf[flip ^ 1], wave, lane);
     flip ^= 1;
     const uint32_t flags = (uint32_t)__builtin_amdgcn_ballot_w64(s_clean[lane & 15] != 0);
@@ -205,10 +167,8 @@ __global__ __launch_bounds__(1024) void k_fused_wide(PathArgs a) {
     all_clean_lo = all_clean_lo && clean_lo;
     all_clean_hi = all_clean_hi && clean_hi;
     finish_tile(A, e_lo, row, clean_lo, acc_lo);
-#ifndef OR_X_MFMA_FRONT
     request(nxt, HP, p2);
     if constexpr (HP == 2) request(nxt, HP + 1, p3);
-#endif
     transform_transposed<K>(C, tbuf[flip], tbuf[flip ^ 1], wave, lane);   // its barrier also orders s_clean for the next worker
     flip ^= 1;
     finish_tile(C, e_hi, row, clean_hi, acc_hi);

@@ -328,44 +328,26 @@ __device__ __forceinline__ void transform_transposed(float (&v)[16], float* ta, 
   // which lets two rows share one LDS instruction (the st64 forms)
   constexpr int RLO = Geo<K>::RLO, PART = tr_wave<K>, XROW = RLO ? TR_ROW : 64;
   static_assert(Geo<K>::R == 16 && Geo<K>::Q >= 1 && Geo<K>::Q <= 4, "2, 4, 8 or 16 wavefronts of 16 registers");
-#ifndef OR_X_NOSTAGES
-#ifdef OR_X_MFMA_FRONT
-  reg_stages(v, 3, 4);
-#else
   reg_stages(v, 0, 4);
-#endif
   lane_stage<0>(v, lane);
   lane_stage<1>(v, lane);
-#endif
   float* mine = ta + wave * PART;
-#ifndef OR_X_NOLDS
 #pragma unroll
   for (int r = 0; r < 16; ++r) mine[r * TR_ROW + lane] = v[r];
   __builtin_amdgcn_wave_barrier();
   const float* back = mine + (lane >> 2) * TR_ROW + (lane & 3);
 #pragma unroll
   for (int r = 0; r < 16; ++r) v[r] = back[r * 4];
-#endif
-#ifndef OR_X_NOSTAGES
   reg_stages(v, 0, 4);
-#endif
   const int rho = lane >> 2;
   float* to = tb + (rho >> RLO) * PART + ((rho & ((1 << RLO) - 1)) + (wave << RLO)) * XROW + (lane & 3);
-#ifndef OR_X_NOLDS
 #pragma unroll
   for (int r = 0; r < 16; ++r) to[r * 4] = v[r];
-#endif
-#ifndef OR_X_NOBARRIER
   __syncthreads();
-#endif
   const float* from = tb + wave * PART + lane;
-#ifndef OR_X_NOLDS
 #pragma unroll
   for (int r = 0; r < 16; ++r) v[r] = from[r * XROW];
-#endif
-#ifndef OR_X_NOSTAGES
   reg_stages(v, RLO, 4);
-#endif
 }
 
 // ------------------------------------------------------------------ tile loads / stores
