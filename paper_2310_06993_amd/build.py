@@ -1,6 +1,6 @@
 """Builds liboptireduce_hip.so for gfx950 with hipcc (cross-compiles without a GPU).
 
-    python -m paper_2310_06993_amd.build [--force]
+    python -m paper_2310_06993_amd.build [--microbench]
 
 Every translation unit is compiled on every call of build(); the block-size classes compile in
 parallel.  Objects go to _build/ (not tracked); the library lands next to this file.
@@ -50,5 +50,20 @@ def build(jobs: int | None = None) -> str:
     return LIB
 
 
+MICROBENCH_SRC = os.path.join(PKG, "microbench", "or_microbench.hip")
+MICROBENCH = os.path.join(PKG, "microbench", "or_microbench")
+
+
+def build_microbench() -> str:
+    """The standalone measurement program behind the design notes (not loaded by the library or the tests)."""
+    cmd = [HIPCC, *[f for f in FLAGS if f not in ("-fPIC", "-fno-gpu-rdc")], MICROBENCH_SRC, "-o", MICROBENCH]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode:
+        raise RuntimeError("hipcc failed: %s\n%s\n%s" % (" ".join(cmd), r.stdout, r.stderr))
+    return MICROBENCH
+
+
 if __name__ == "__main__":
     print(build())
+    if "--microbench" in sys.argv:
+        print(build_microbench())
