@@ -1,7 +1,7 @@
 // One block-size class of kernels (compile with -DOR_K=0, 11, 12, ... 16).
 #include "launch_table.hpp"
 #if OR_K > 14
-#include "rht_fused_wide.hpp"
+#include "rht_fused_mx.hpp"
 #endif
 
 #ifndef OR_K
@@ -118,7 +118,7 @@ OR_FUSED_LAUNCHER(fusb_bf16, BatchArgs, k_fused_batched)
     return launch_kernel(kernel, dim3((unsigned)grid), dim3(G::THREADS), s, pos, a);         \
   }
 OR_PAIR_LAUNCHER(fus_f32, (k_fused_pairs<K, float>))
-OR_PAIR_LAUNCHER(fus_bf16, (k_fused_wide<K>))
+OR_PAIR_LAUNCHER(fus_bf16, (k_fused_mx<K>))
 #endif
 }  // namespace
 

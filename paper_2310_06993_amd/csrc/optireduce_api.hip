@@ -179,41 +179,14 @@ __global__ __launch_bounds__(256) void k_zero_u64n(unsigned long long* p, int n)
 // first_counter + c, 16 bytes, at tab + 16 c -- so bit j of 64-bit word w is the sign of entry 64 w + j
 // counted from the first entry.  The fused kernels for blocks above 2^14 read it with scalar loads.
 __global__ __launch_bounds__(256) void k_sign_table(uint4* __restrict__ tab, u64 seed, u64 first_counter,
-                                                    u64 n_counters) {
+                                                    u64 n_counters, unsigned* __restrict__ flags, u64 n_flag_words) {
   const u64 c = (u64)blockIdx.x * 256 + threadIdx.x;
+  if (c < n_flag_words) flags[c] = 0;   // the words of the pair hand-over of the bf16 kernel for 2^16 blocks
   if (c >= n_counters) return;
   const u64 ctr = first_counter + c;
   const ordev::u32x4 w =
       ordev::philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), 0u, 0u, (uint32_t)seed, (uint32_t)(seed >> 32));
   tab[c] = make_uint4(w.a, w.b, w.c, w.d);
-}
-
-// The same signs in the order the bf16 kernels for blocks above 2^14 hold their registers: word w belongs to
-// the 1024-entry slice w / 16 and its register r = w % 16; bit l is the sign of entry
-// slice * 1024 + (r / 8) * 512 + l * 8 + (r % 8), counted from `first_entry` (a multiple of 512).
-// Also clears the `n_flag_words` words of the pair hand-over that the fused kernel for 2^16 blocks uses.
-__global__ __launch_bounds__(256) void k_sign_table_strided(u64* __restrict__ tab, u64 seed, u64 first_entry, u64 n_words,
-                                                            unsigned* __restrict__ flags, u64 n_flag_words) {
-  const u64 w = (u64)blockIdx.x * 256 + threadIdx.x;
-  if (w < n_flag_words) flags[w] = 0;
-  if (w >= n_words) return;
-  const u64 slice = w >> 4;
-  const int r = (int)(w & 15), j = r & 7;
-  const u64 ctr0 = (first_entry + slice * 1024 + (u64)(r >> 3) * 512) >> 7;   // four counters cover the run of 512
-  u64 bits = 0;
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const u64 ctr = ctr0 + q;
-    const ordev::u32x4 o =
-        ordev::philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), 0u, 0u, (uint32_t)seed, (uint32_t)(seed >> 32));
-    const uint32_t word[4] = {o.a, o.b, o.c, o.d};
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-      for (int s8 = 0; s8 < 4; ++s8)   // entry q*128 + t*32 + s8*8 + j of the run sits on lane q*16 + t*4 + s8
-        bits |= (u64)((word[t] >> (j + 8 * s8)) & 1u) << (q * 16 + t * 4 + s8);
-  }
-  tab[w] = bits;
 }
 
 // Sec. 3.4 loss monitoring: total of the received counts of a shard (16 counts per lane, byte sums
@@ -460,13 +433,13 @@ or_status run_path(bool fused, const T* in, const uint32_t* masks, int N, u64 L,
   d.unit0 = units;   // shards hold whole blocks: no tile of the decode needs bounds checks
   if (fused && bf16) {
     // bf16: one kernel does everything.  Workspace: [hand-over slots of the workgroup pairs, 4 L bytes, k = 16 only]
-    // [sign table in register order, L/8 bytes][pair flags, 8 bytes a block]
-    const u64 words = L >> 6, nflags = k == 16 ? 2 * (L >> 16) : 0;
+    // [sign stream of the shard, L/8 bytes][pair flags, 8 bytes a block]
+    const u64 counters = L >> 7, nflags = k == 16 ? 2 * (L >> 16) : 0;   // one thread per Philox counter
     unsigned* flags = (unsigned*)(ws_cnt + (L / 8 + 255) / 256 * 256);
-    const u64 blocks = ((words > nflags ? words : nflags) + 255) / 256;
+    const u64 blocks = ((counters > nflags ? counters : nflags) + 255) / 256;
     if (blocks > 0x7FFFFFFFull) return OR_ERR_SHAPE;
-    if (hipError_t e = orhost::launch_kernel(k_sign_table_strided, dim3((unsigned)blocks), dim3(256), s, first, (u64*)ws_cnt,
-                                             seed, base, words, flags, nflags))
+    if (hipError_t e = orhost::launch_kernel(k_sign_table, dim3((unsigned)blocks), dim3(256), s, first, (uint4*)ws_cnt, seed,
+                                             base >> 7, counters, flags, nflags))
       return finish(e);
     a.sign_tab = (const u64*)ws_cnt;
     a.mean_out = ws_f32;
@@ -478,7 +451,7 @@ or_status run_path(bool fused, const T* in, const uint32_t* masks, int N, u64 L,
     const u64 counters = L >> 7;
     if ((counters + 255) / 256 > 0x7FFFFFFFull) return OR_ERR_SHAPE;
     if (hipError_t e = orhost::launch_kernel(k_sign_table, dim3((unsigned)((counters + 255) / 256)), dim3(256), s,
-                                             first, (uint4*)ws_cnt, seed, base >> 7, counters))
+                                             first, (uint4*)ws_cnt, seed, base >> 7, counters, (unsigned*)nullptr, (u64)0))
       return finish(e);
     a.sign_tab = (const u64*)ws_cnt;
     if (k == 15)   // two tiles per block: the fused kernel decodes as well
