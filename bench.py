@@ -236,9 +236,9 @@ def profiled_traffic(workload):
     """HBM bytes per launch of the dominant kernel as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
     (scaled by a known-size copy); taken from the committed summary under profiles/, null if there is none."""
     import re
-    path = os.path.join(ROOT, "profiles", "k_fused_%s.md" % workload)
+    path = os.path.join(ROOT, "profiles", "fused_path_%s.md" % workload)
     try:
-        m = re.search(r"traffic = (\d+) bytes per launch", open(path).read())
+        m = re.search(r"traffic = (\d+) bytes per (?:launch|step)", open(path).read())
         return int(m.group(1)) if m else None
     except OSError:
         return None
@@ -249,13 +249,14 @@ def roofline(cfg, L, nbytes, kern):
     k (N + 1)/N + 1 additions.  At the chip's peaks (8 TB/s; 256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz = 78.6e12
     fp32 additions per second: an addition is half of the fused multiply-add that the published 157.3 TFLOP/s
     counts) the bytes take longer than the additions for all five workloads, so HBM is the roof.  The second
-    figure is reported beside it because the kernels for 2^15 / 2^16 blocks spend more instructions than that
-    minimum (sign flips, conversions, rounding, count handling) and are limited by vector-ALU issue in practice."""
+    figure is reported beside it because the kernels for 2^15 / 2^16 blocks spend several times that minimum in
+    instructions (sign flips, conversions, rounding, exchanges through LDS) and sit far below the HBM roof."""
     N, k = cfg.workers, cfg.block_log2
     adds = (k * (N + 1) / N + 1.0) * N * L
     peak_adds = 256 * 4 * 32 * 2.4e9
     names = {True: "k_fused (one launch per step)",
-             False: "k_sign_table + k_fused_pairs + k_decode_block (one step; the fused kernel is >= 85 % of it)"}
+             False: "k_sign_table + k_fused_mx (one step; the fused kernel is 99 % of it)" if cfg.dtype != "f32"
+             else "k_sign_table + k_fused_pairs (+ k_decode_block for 2^16 blocks), one step"}
     return {"bound": "hbm", "achieved": nbytes / kern / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": nbytes / kern / 1e9 / HBM_PEAK_GBPS, "traffic": profiled_traffic(cfg.name),
             "kernel": names[cfg.block_log2 <= 14], "avg_launch_us": kern * 1e6,
