@@ -170,18 +170,23 @@ __global__ __launch_bounds__(1024) void k_fused_mx(PathArgs a) {
 
   u32x4v p[NCH];
   uint32_t mw;
-  const unsigned lane_load = lane_part >> 3;   // in 16-byte units
+  // Loads go through buffer descriptors built per worker in scalar registers: one vector register (the lane's byte
+  // offset) then serves every load of every worker, where flat addresses would take a 64-bit pair per stream.
+  const int lane_bytes = (int)lane_part * 2;
   auto request = [&](int i, int ch0, int ch1) {
-    const u32x4v* src = (const u32x4v*)(grads + (u64)i * L + wave_entry);
+    const __amdgpu_buffer_rsrc_t rs =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(grads + (u64)i * L + wave_entry), 0, PARTS * T * 2, 0x00020000);
 #pragma unroll
-    for (int ch = ch0; ch < ch1; ++ch) {
-      if constexpr (HP == 2) p[ch] = src[lane_load + ch * 16];            // read by the other workgroup of the block too
-      else p[ch] = __builtin_nontemporal_load(src + lane_load + ch * 16);
-    }
+    for (int ch = ch0; ch < ch1; ++ch)   // four tiles per block: read by the other workgroup of the block too -> no nontemporal hint
+      p[ch] = __builtin_bit_cast(u32x4v, __builtin_amdgcn_raw_buffer_load_b128(rs, lane_bytes, ch * 256, HP == 2 ? 0 : 2));
   };
   // received bits of the two output tiles: 512 words each, wavefronts 0..7 look at the first, 8..15 at the second
   const u64 words_entry = ((wave < 8 ? e_lo : e_hi) >> 5) + (u64)((wave & 7) * 64);
-  auto request_words = [&](int i) { mw = (a.masks + (u64)i * mrow + words_entry)[(unsigned)lane]; };
+  auto request_words = [&](int i) {
+    const __amdgpu_buffer_rsrc_t rs =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(a.masks + (u64)i * mrow + words_entry), 0, 256, 0x00020000);
+    mw = __builtin_amdgcn_raw_buffer_load_b32(rs, lane * 4, 0, 0);
+  };
   request(0, 0, NCH);
   request_words(0);
 
@@ -189,12 +194,11 @@ __global__ __launch_bounds__(1024) void k_fused_mx(PathArgs a) {
   const int y_lane = ((lane >> 2) & 3) * 32 + (lane & 3) * 8 + ((lane >> 4) & 1) * 4 + (wave & 3) + (wave >> 2) * 128;
   // encoded values of both arrays -> wire rounding -> sum under the received bits
   auto finish = [&](float (&v)[R], int arr, const uint32_t* row, bool clean, float (&acc)[R]) {
+    // one conversion per value with the result in the HIGH half (the low half converts a zero): that is the fp32
+    // pattern of the rounded value, no unpacking
 #pragma unroll
-    for (int r = 0; r < R; r += 2) {
-      const uint32_t pk = scale_first ? pack_bf16x2(v[r] * a.scale, v[r + 1] * a.scale) : pack_bf16x2(v[r], v[r + 1]);
-      v[r] = bf16_lo(pk);
-      v[r + 1] = bf16_hi(pk);
-    }
+    for (int r = 0; r < R; ++r)
+      v[r] = __builtin_bit_cast(float, pack_bf16x2(0.0f, scale_first ? v[r] * a.scale : v[r]));
     if (clean) {
 #pragma unroll
       for (int r = 0; r < R; ++r) acc[r] += v[r];
@@ -213,6 +217,10 @@ __global__ __launch_bounds__(1024) void k_fused_mx(PathArgs a) {
     const uint32_t* row = a.masks + (u64)i * mrow;
     const int nxt = i + 1 < a.N ? i + 1 : i;
     float X[R], Y[R];
+    // The LDS addresses of the transforms depend on the lane alone; recomputing them each trip (a handful of
+    // instructions) keeps them out of the registers that the trip needs for data
+    int lane_t = lane;
+    asm volatile("" : "+v"(lane_t));
     // The masks are rebuilt from the sign bytes for every worker (3 instructions a pair).  Left alone the compiler
     // computes all of them once before the loop -- and then has 32 registers too many and keeps them in scratch.
 #pragma unroll
@@ -255,13 +263,13 @@ __global__ __launch_bounds__(1024) void k_fused_mx(PathArgs a) {
       }
     }
     // left to do: register bits 2, 3 (index bits 7, 8), lane bits 0..3 (index bits 3..6), the wave bits (10..13)
-    transform_transposed_sel<K, 0xC, 0x3>(X, tbuf[flip], tbuf[flip ^ 1], wave, lane);
+    transform_transposed_sel<K, 0xC, 0x3>(X, tbuf[flip], tbuf[flip ^ 1], wave, lane_t);
     flip ^= 1;
-    const bool clean = ((uint32_t)__builtin_amdgcn_ballot_w64(s_clean[lane & 15] != 0) & 0xFFFFu) == 0xFFFFu;
+    const bool clean = ((uint32_t)__builtin_amdgcn_ballot_w64(s_clean[lane_t & 15] != 0) & 0xFFFFu) == 0xFFFFu;
     all_clean = all_clean && clean;
     finish(X, 0, row, clean, accX);
     request(nxt, NCH / 2, NCH);
-    transform_transposed_sel<K, 0xC, 0x3>(Y, tbuf[flip], tbuf[flip ^ 1], wave, lane);   // its barrier also orders s_clean
+    transform_transposed_sel<K, 0xC, 0x3>(Y, tbuf[flip], tbuf[flip ^ 1], wave, lane_t);   // its barrier also orders s_clean
     flip ^= 1;
     finish(Y, 1, row, clean, accY);
   }
