@@ -250,6 +250,49 @@ def test_fused_worker_counts_and_64_bit_seeds(b, orc, k, N, blocks):
     assert rel_l2(to_np(out), want) <= TOL["f32"]
 
 
+@pytest.mark.parametrize("k,N,blocks", [(16, 1, 1), (16, 2, 9), (16, 9, 17), (15, 1, 3), (15, 9, 4), (16, 255, 1), (15, 64, 2)])
+def test_fused_bf16_large_blocks_worker_counts_and_loss_patterns(b, orc, k, N, blocks):
+    """The bf16 kernel for blocks of 2^15 / 2^16 entries decides per worker whether anything of its two output tiles
+    was lost: workers with nothing lost, with single entries lost, with a whole tile lost and with everything lost
+    side by side; one worker, odd and large worker counts, more blocks than a group of 8 (the placement of the
+    workgroups of a block), a seed with high bits set and a base index beyond 2^32."""
+    B, T = 1 << k, 1 << 14
+    L = blocks * B
+    rng = np.random.default_rng(7000 + 31 * k + N)
+    raw = _bf16_bits((rng.standard_normal((N, L)) * 1e-4).astype(np.float32))
+    recv = np.ones((N, L), bool)
+    for i in range(N):
+        kind = i % 5
+        if kind == 1:                                   # scattered single entries
+            recv[i] = rng.random(L) > 0.01
+        elif kind == 2:                                 # one whole tile, in every second block
+            for blk in range(0, blocks, 2):
+                t = (i // 5 + blk) % (B // T)
+                recv[i, blk * B + t * T: blk * B + (t + 1) * T] = False
+        elif kind == 3:                                 # a 512-entry packet here and there
+            ok = rng.random(L // 512) > 0.03
+            recv[i] = np.repeat(ok, 512)
+        elif kind == 4 and N > 4:                       # nothing of this worker arrived
+            recv[i] = False
+    masks = pack_mask_np(recv)
+    seed, base = 0xF00DFACE12345678, (1 << 33) + 5 * B
+    want, want_count = orc.fused_path(raw, masks, k, seed, base)
+    out = torch.full((L,), float("nan"), dtype=torch.bfloat16, device=dev())
+    count = torch.full((L,), 77, dtype=torch.uint8, device=dev())
+    total = torch.full((1,), -1, dtype=torch.int64, device=dev())
+    gd, md, ws = _dev_bf16(raw), masks_to_dev(masks), _workspace(b, L, k)   # (the descriptor holds plain addresses)
+    arr = b.make_buckets([(gd, md, out, count, L, seed, base)])
+    b.or_fused_path_batched_monitored(arr, 1, N, k, True, total, ws)
+    assert np.array_equal(to_np(count), want_count)
+    assert int(total.item()) == int(want_count.sum(dtype=np.int64)) == int(recv.sum())
+    assert rel_l2(to_np(out), want) <= TOL["bf16"]
+    # block by block as well: a block with a wrong factor would hide in the total
+    for blk in range(blocks):
+        sl = slice(blk * B, (blk + 1) * B)
+        assert rel_l2(to_np(out[sl]), want[sl]) <= TOL["bf16"], blk
+    assert (to_np(out) != want).mean() < 0.05          # bf16 values: almost all identical, the rest one step apart
+
+
 def test_three_calls_equal_fused(b, orc):
     from paper_2310_06993_amd import workloads as wl
     cfg = wl.CONFIGS["tiny"]
