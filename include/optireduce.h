@@ -60,7 +60,11 @@ enum {
 /* n rounded up to a whole number of blocks of 2^block_log2 entries (0 if block_log2 is invalid). */
 uint64_t or_padded_len(uint64_t n, int block_log2);
 /* Bytes of device workspace that or_reduce_decode* / or_fused_path* need for this shard length and
- * block size: 0 for block_log2 <= 14, else room for the fp32 sums/means and the counts. */
+ * block size: 0 for block_log2 <= 14, else 5 bytes per shard entry (rounded up to 256-byte parts).  What
+ * the kernels keep there (fp32 sums or means and counts; the shard's sign stream; for the bf16 fused
+ * path with block_log2 = 16 what the two workgroups of a block hand to each other, and their flags) is
+ * written before it is read within one call: the workspace needs no initialisation, and calls that may
+ * overlap in time need workspaces of their own. */
 size_t or_workspace_bytes(uint64_t shard_len, int block_log2);
 const char* or_status_string(or_status s);
 int or_version(void);
