@@ -16,8 +16,8 @@
 //
 // Positions.  A product leaves D[i][n] on lane l = (n, i2, i3), register i0 i1, with n = l & 15 the untouched index
 // bits 3..6.  With the chunk number ch (index bits 7.. of the wavefront's slice) the 32 registers of a lane are two
-// arrays X, Y of 16: register 4 ch' + r.  The remaining stages run as in transform_transposed (which swaps the bits
-// held by the register number with those held by the wave number), skipping the bits the product has done:
+// arrays X, Y of 16: register 4 ch' + r.  The remaining stages (transform_dpp_sel) swap the bits held by the register
+// number with those held by the wave number, as transform_transposed does, and skip the bits the product has done:
 //     after the encode   array a, wave w, register r, lane l   is encoded entry
 //         y = r*1024 + a*512 + (w>>2)*128 + ((l>>2)&3)*32 + (l&3)*8 + ((l>>4)&1)*4 + (w&3)
 //         of the output tile chosen by lane bit 5 (2^16: tiles h, h+2; 2^15: tiles 0, 1);
@@ -51,11 +51,14 @@ struct PairFlags {
 };
 constexpr unsigned kPairSpinLimit = 1u << 22;   // polls of `ready` before the waiting workgroup gives up
 
-// the stages of transform_transposed selected by two masks: FIRST = register bits transformed before the
-// transposition, MID = the register bits (lane bits 2..5 before it) transformed after it
-template <int K, int FIRST, int MID>
-__device__ __forceinline__ void transform_transposed_sel(float (&v)[16], float* ta, float* tb, int wave, int lane) {
-  constexpr int RLO = Geo<K>::RLO, PART = tr_wave<K>, XROW = RLO ? TR_ROW : 64;
+// The stages that are left after the matrix-core product: the register bits in FIRST, the lane bits 0..3 as DPP
+// stages, the wave bits after the plain exchange between wavefronts (register and wave bits swap, lanes stay in
+// place: the same final positions as transform_transposed).  Measured against the form with the transposition inside
+// the wavefront (lane bits 2, 3 as register stages): half the LDS traffic for 64 more half-rate vector instructions,
+// 6 % less time -- a trip's vector, LDS and memory phases hardly overlap (one workgroup per CU, its wavefronts in step).
+// The result on lane l carries the factor lane_sigma(l, 4).
+template <int K, int FIRST>
+__device__ __forceinline__ void transform_dpp_sel(float (&v)[16], float* xbuf, int wave, int lane) {
   static_assert(Geo<K>::R == 16 && Geo<K>::Q == 4, "16 wavefronts of 16 registers");
   if constexpr (FIRST & 1) reg_stage<0>(v);
   if constexpr (FIRST & 2) reg_stage<1>(v);
@@ -63,26 +66,10 @@ __device__ __forceinline__ void transform_transposed_sel(float (&v)[16], float* 
   if constexpr (FIRST & 8) reg_stage<3>(v);
   lane_stage<0>(v, lane);
   lane_stage<1>(v, lane);
-  float* mine = ta + wave * PART;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) mine[r * TR_ROW + lane] = v[r];
-  __builtin_amdgcn_wave_barrier();
-  const float* back = mine + (lane >> 2) * TR_ROW + (lane & 3);
-#pragma unroll
-  for (int r = 0; r < 16; ++r) v[r] = back[r * 4];
-  if constexpr (MID & 1) reg_stage<0>(v);
-  if constexpr (MID & 2) reg_stage<1>(v);
-  if constexpr (MID & 4) reg_stage<2>(v);
-  if constexpr (MID & 8) reg_stage<3>(v);
-  const int rho = lane >> 2;
-  float* to = tb + (rho >> RLO) * PART + ((rho & ((1 << RLO) - 1)) + (wave << RLO)) * XROW + (lane & 3);
-#pragma unroll
-  for (int r = 0; r < 16; ++r) to[r * 4] = v[r];
-  __syncthreads();
-  const float* from = tb + wave * PART + lane;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) v[r] = from[r * XROW];
-  reg_stages(v, RLO, 4);
+  lane_stage<2>(v, lane);
+  lane_stage<3>(v, lane);
+  exchange<K, true, false>(v, xbuf, wave, lane);
+  reg_stages(v, 0, 4);
 }
 
 // (sign bit of the even entry) << 15 | (sign bit of the odd entry) << 31 for pair d = 0..3 of a lane's 8 entries,
@@ -263,13 +250,13 @@ __global__ __launch_bounds__(1024) void k_fused_mx(PathArgs a) {
       }
     }
     // left to do: register bits 2, 3 (index bits 7, 8), lane bits 0..3 (index bits 3..6), the wave bits (10..13)
-    transform_transposed_sel<K, 0xC, 0x3>(X, tbuf[flip], tbuf[flip ^ 1], wave, lane_t);
+    transform_dpp_sel<K, 0xC>(X, tbuf[flip], wave, lane_t);
     flip ^= 1;
     const bool clean = ((uint32_t)__builtin_amdgcn_ballot_w64(s_clean[lane_t & 15] != 0) & 0xFFFFu) == 0xFFFFu;
     all_clean = all_clean && clean;
     finish(X, 0, row, clean, accX);
     request(nxt, NCH / 2, NCH);
-    transform_transposed_sel<K, 0xC, 0x3>(Y, tbuf[flip], tbuf[flip ^ 1], wave, lane_t);   // its barrier also orders s_clean
+    transform_dpp_sel<K, 0xC>(Y, tbuf[flip], wave, lane_t);   // its barrier also orders s_clean
     flip ^= 1;
     finish(Y, 1, row, clean, accY);
   }
@@ -315,7 +302,7 @@ __global__ __launch_bounds__(1024) void k_fused_mx(PathArgs a) {
     __builtin_nontemporal_store(c_hi, (u32x4v*)(a.count_out + e_hi) + threadIdx.x);
     __syncthreads();   // the staging area is part of the transform buffers: all reads before anyone transforms again
   };
-  const float post = sigma * (scale_first ? 1.0f : a.scale);
+  const float post = lane_sigma(lane, 4) * (scale_first ? 1.0f : a.scale);   // the sign that the DPP stages leave on a lane
   finalize_mean(accX, cntX, full, post);
   finalize_mean(accY, cntY, full, post);
   __syncthreads();   // every wavefront has read the last exchange of the loop before the buffers are used again
