@@ -100,10 +100,13 @@ static void streams() {
 }
 
 // ------------------------------------------------------------------ issue costs
-enum { OP_ADD, OP_FMA, OP_XOR, OP_ADD_DPP, OP_CNDMASK_SGPR, OP_LSHL, OP_CVT_PK_BF16, OP_MUL_LO, OP_DOT2C, OP_MFMA_BF16, OP_MFMA_F32, OP_COUNT };
+enum { OP_ADD, OP_FMA, OP_XOR, OP_ADD_DPP, OP_CNDMASK_SGPR, OP_LSHL, OP_CVT_PK_BF16, OP_MUL_LO, OP_DOT2C, OP_MFMA_BF16, OP_MFMA_F32,
+       OP_DPP_ROR8, OP_DPP_SHL4, OP_DPP_MIRROR, OP_DPP_HALF_MIRROR, OP_SWIZZLE, OP_COUNT };
 static const char* op_name[OP_COUNT] = {"v_add_f32", "v_fma_f32", "v_xor_b32", "v_add_f32 (DPP quad_perm)", "v_cndmask_b32 (SGPR mask, neg)",
                                         "v_lshlrev_b32", "v_cvt_pk_bf16_f32", "v_mul_lo_u32", "v_dot2c_f32_bf16",
-                                        "v_mfma_f32_16x16x32_bf16", "v_mfma_f32_16x16x4_f32"};
+                                        "v_mfma_f32_16x16x32_bf16", "v_mfma_f32_16x16x4_f32", "v_add_f32 (DPP row_ror:8)",
+                                        "v_add_f32 (DPP row_shl:4, bank-masked)", "v_add_f32 (DPP row_mirror)",
+                                        "v_add_f32 (DPP row_half_mirror)", "ds_swizzle_b32 (lane ^ 4) + v_add_f32"};
 template <int OP>
 __global__ __launch_bounds__(1024) void mb_issue(float* out, int iters, unsigned long long mask) {
   float v[16];
@@ -127,6 +130,11 @@ __global__ __launch_bounds__(1024) void mb_issue(float* out, int iters, unsigned
         else if (OP == OP_CVT_PK_BF16) asm volatile("v_cvt_pk_bf16_f32 %0, %0, %1" : "+v"(v[i]) : "v"(s));
         else if (OP == OP_MUL_LO) asm volatile("v_mul_lo_u32 %0, %0, %1" : "+v"(v[i]) : "v"(s));
         else if (OP == OP_DOT2C) v[i] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf2, 0x3F803F80u), __builtin_bit_cast(bf2, 0x00003F80u), v[i], false);
+        else if (OP == OP_DPP_ROR8) asm volatile("v_add_f32_dpp %0, %0, %1 row_ror:8 row_mask:0xf bank_mask:0xf" : "+v"(v[i]) : "v"(s));
+        else if (OP == OP_DPP_SHL4) asm volatile("v_add_f32_dpp %0, %0, %1 row_shl:4 row_mask:0xf bank_mask:0x5" : "+v"(v[i]) : "v"(s));
+        else if (OP == OP_DPP_MIRROR) asm volatile("v_add_f32_dpp %0, %0, %1 row_mirror row_mask:0xf bank_mask:0xf" : "+v"(v[i]) : "v"(s));
+        else if (OP == OP_DPP_HALF_MIRROR) asm volatile("v_add_f32_dpp %0, %0, %1 row_half_mirror row_mask:0xf bank_mask:0xf" : "+v"(v[i]) : "v"(s));
+        else if (OP == OP_SWIZZLE) v[i] = v[i] + __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v[i]), 0x101F));
         else if (OP == OP_MFMA_BF16) { if ((i & 7) == 0) c[(r * 2 + i / 8) & 3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c[(r * 2 + i / 8) & 3], 0, 0, 0); }
         else if (OP == OP_MFMA_F32) { if ((i & 7) == 0) c[(r * 2 + i / 8) & 3] = __builtin_amdgcn_mfma_f32_16x16x4f32(s, v[0], c[(r * 2 + i / 8) & 3], 0, 0, 0); }
       }
@@ -154,6 +162,8 @@ static void issue(float* out) {
   run_issue<OP_ADD>(out); run_issue<OP_FMA>(out); run_issue<OP_XOR>(out); run_issue<OP_ADD_DPP>(out);
   run_issue<OP_CNDMASK_SGPR>(out); run_issue<OP_LSHL>(out); run_issue<OP_CVT_PK_BF16>(out); run_issue<OP_MUL_LO>(out);
   run_issue<OP_DOT2C>(out); run_issue<OP_MFMA_BF16>(out); run_issue<OP_MFMA_F32>(out);
+  run_issue<OP_DPP_ROR8>(out); run_issue<OP_DPP_SHL4>(out); run_issue<OP_DPP_MIRROR>(out); run_issue<OP_DPP_HALF_MIRROR>(out);
+  run_issue<OP_SWIZZLE>(out);
 }
 
 // ------------------------------------------------------------------ overlap of matrix-core and vector work
